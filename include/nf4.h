@@ -1,0 +1,119 @@
+/*
+ * nf4.h -- C-ABI of libnf4: blockwise NF4 (4-bit NormalFloat) dequantisation
+ * for AMD MI355X (gfx950).
+ *
+ * Paper: "Fast NF4 Dequantization Kernels for Large Language Model Inference".
+ *
+ * Format (Sec. II-B; Algorithm 1):
+ *   - 16 FP32 levels in [-1, 1] (normal quantiles; level 7 is 0, level 0 is -1,
+ *     level 15 is +1).
+ *   - Two 4-bit codes per byte; byte j holds element 2j in its HIGH nibble and
+ *     element 2j+1 in its LOW nibble.
+ *   - One scale ("absmax") per block of `blocksize` consecutive elements of the
+ *     flat tensor (the paper uses 64).
+ *   - value(i) = level[code(i)] * scale(i / blocksize), one FP32 multiply, then
+ *     one round-to-nearest-even conversion to FP16 (the paper's output type) or
+ *     BF16.
+ *   - Double-quantised scales (not in the paper; this library's definition):
+ *     scale(b) = code2[absmax_q8[b]] * scale2[b / 256] + offset[0], an FP32
+ *     multiply and an FP32 add, each rounded once (never fused).
+ *
+ * Conventions for every entry point
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller.  The library
+ *     never allocates, frees or synchronises; it only enqueues kernels on
+ *     `stream` (a hipStream_t passed as void*; NULL = the default stream) and
+ *     returns at once.  Inputs must stay valid and unchanged until that work
+ *     has run; inputs and outputs must not overlap.
+ *   - The return value is an nf4_status.  Nothing aborts or throws.  Arguments
+ *     are checked on the host before anything is launched: a call that returns
+ *     an error other than NF4_ERR_HIP has launched nothing.
+ *   - n == 0 (or N == 0) returns NF4_OK without launching.
+ *   - `blocksize` must be a power of two in [64, 4096] (tuned for 64).
+ *   - `packed` and the 16-bit outputs must be 16-byte aligned; FP32 arrays
+ *     4-byte aligned (else NF4_ERR_ALIGN).
+ *   - A tensor with n elements has ceil(n/2) packed bytes, nb = ceil(n /
+ *     blocksize) scales and ceil(nb / 256) second-level scales.  Nothing is read
+ *     past those sizes or written past out[n-1]; with an odd n the low nibble of
+ *     the last byte is ignored (Sec. V-A: sizes that do not fill a tile are
+ *     handled by predication).
+ */
+#ifndef NF4_H
+#define NF4_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    NF4_OK = 0,
+    NF4_ERR_NULL = 1,      /* a required pointer is NULL */
+    NF4_ERR_SIZE = 2,      /* negative element count, or a size beyond the supported range */
+    NF4_ERR_BLOCKSIZE = 3, /* blocksize not a power of two in [64, 4096] */
+    NF4_ERR_DTYPE = 4,     /* out_dtype is neither NF4_FP16 nor NF4_BF16 */
+    NF4_ERR_ALIGN = 5,     /* a pointer is not aligned as stated above */
+    NF4_ERR_SHAPE = 6,     /* GEMV: K not a multiple of blocksize, or B outside [1, 16] */
+    NF4_ERR_HIP = 7        /* the HIP runtime refused the launch; see nf4_last_hip_error */
+} nf4_status;
+
+typedef enum { NF4_FP16 = 0, NF4_BF16 = 1 } nf4_dtype;
+
+/*
+ * Algorithm 1 (with the per-64-element scale of Sec. II-B):
+ *   out[i] = rne16( level[code(i)] * absmax[i / blocksize] ),  0 <= i < n.
+ * packed : uint8[ceil(n/2)], absmax : float[ceil(n/blocksize)],
+ * out    : uint16[n] holding FP16 or BF16 bit patterns per out_dtype.
+ */
+int nf4_dequantize(const uint8_t* packed, const float* absmax, int blocksize, int64_t n,
+                   void* out, int out_dtype, void* stream);
+
+/*
+ * Same as nf4_dequantize with double-quantised scales:
+ *   scale(b) = code2[absmax_q8[b]] * scale2[b / 256] + offset[0].
+ * absmax_q8 : uint8[nb], scale2 : float[ceil(nb/256)], offset : float[1],
+ * code2 : float[256] (the caller's map of the 8-bit code).
+ */
+int nf4_dequantize_dq(const uint8_t* packed, const uint8_t* absmax_q8, const float* scale2,
+                      const float* offset, const float* code2, int blocksize, int64_t n,
+                      void* out, int out_dtype, void* stream);
+
+/*
+ * Fused dequantise + decode GEMV (not in the paper, which dequantises into a
+ * temporary before a dense matmul, Sec. III-C; here W is never materialised):
+ *   y[b][r] = rne_fp16( sum_k x[b][k] * W[r][k] ),
+ *   W[r][k] = level[code(r*K + k)] * scale((r*K + k) / blocksize)   (FP32),
+ * FP32 accumulation, W is [N][K] row-major with double-quantised scales as in
+ * nf4_dequantize_dq.  x : FP16 [B][K], y : FP16 [B][N], 1 <= B <= 16, K > 0
+ * and K % blocksize == 0 (else NF4_ERR_SHAPE).  packed and x must be 16-byte
+ * aligned.
+ */
+int nf4_dequant_gemv(const uint8_t* packed, const uint8_t* absmax_q8, const float* scale2,
+                     const float* offset, const float* code2, int blocksize, int64_t N,
+                     int64_t K, const void* x, int B, void* y, void* stream);
+
+/*
+ * Reference-quality (untuned) quantiser, the forward direction of Sec. II-B:
+ * per block absmax = max |src|, code = nearest level to src / absmax (FP32
+ * distance, ties to the lower index, all-zero block -> absmax 0 and code 7,
+ * unused last low nibble -> 7).  Writes packed[ceil(n/2)] and absmax[nb].
+ * If absmax_q8 != NULL it also double-quantises the scales: code2[u] = (u -
+ * 127)/127, offset = mean(absmax), scale2[g] = max |absmax - offset| over the
+ * group, absmax_q8 = 127 + clamp(rint(127 * (absmax - offset) / scale2), -127,
+ * 127); then scale2, offset and code2 must be non-NULL too.  absmax is always
+ * required (it is the first-level result the second level encodes).
+ */
+int nf4_quantize_ref(const float* src, int64_t n, int blocksize, uint8_t* packed, float* absmax,
+                     uint8_t* absmax_q8, float* scale2, float* offset, float* code2,
+                     void* stream);
+
+/* hipError_t (as int) behind the most recent NF4_ERR_HIP on the calling thread; 0 if none. */
+int nf4_last_hip_error(void);
+
+/* Static, NUL-terminated name of a status code ("NF4_OK", ...); "NF4_ERR_UNKNOWN" otherwise. */
+const char* nf4_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NF4_H */

@@ -258,11 +258,13 @@ static double f16_bits_to_double(uint16_t h) {
     return sign ? -v : v;
 }
 
-void nf4o_dequant_gemv(const uint8_t *packed, const uint8_t *absmax_q8, const float *scale2,
-                       const float *offset, const float *code2, int blocksize, int64_t N,
-                       int64_t K, const uint16_t *x, int B, uint16_t *y, double *y_f64) {
+/* Rows [r_first, r_first + r_count) only; y and y_f64 are [B][r_count]. */
+void nf4o_dequant_gemv_rows(const uint8_t *packed, const uint8_t *absmax_q8, const float *scale2,
+                            const float *offset, const float *code2, int blocksize, int64_t K,
+                            const uint16_t *x, int B, int64_t r_first, int64_t r_count,
+                            uint16_t *y, double *y_f64) {
     for (int b = 0; b < B; ++b) {
-        for (int64_t r = 0; r < N; ++r) {
+        for (int64_t r = r_first; r < r_first + r_count; ++r) {
             double acc = 0.0;
             for (int64_t k = 0; k < K; ++k) {
                 int64_t i = r * K + k;
@@ -270,8 +272,15 @@ void nf4o_dequant_gemv(const uint8_t *packed, const uint8_t *absmax_q8, const fl
                 float w = NF4_LEVEL[code_of(packed, i)] * scale;
                 acc += f16_bits_to_double(x[(int64_t)b * K + k]) * (double)w;
             }
-            if (y_f64) y_f64[(int64_t)b * N + r] = acc;
-            if (y) y[(int64_t)b * N + r] = nf4o_f32_to_f16((float)acc);
+            int64_t o = (int64_t)b * r_count + (r - r_first);
+            if (y_f64) y_f64[o] = acc;
+            if (y) y[o] = nf4o_f32_to_f16((float)acc);
         }
     }
+}
+
+void nf4o_dequant_gemv(const uint8_t *packed, const uint8_t *absmax_q8, const float *scale2,
+                       const float *offset, const float *code2, int blocksize, int64_t N,
+                       int64_t K, const uint16_t *x, int B, uint16_t *y, double *y_f64) {
+    nf4o_dequant_gemv_rows(packed, absmax_q8, scale2, offset, code2, blocksize, K, x, B, 0, N, y, y_f64);
 }

@@ -1,0 +1,51 @@
+// Device-side pieces shared by the gfx950 kernels: the level table, nibble
+// handling and the round-to-nearest-even narrowing conversions.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/nf4.h"
+
+namespace nf4 {
+
+constexpr int kWave = 64;
+
+// Sec. II-B: the 16 NormalFloat levels (normal quantiles scaled to [-1, 1]),
+// as binary32 bit patterns so that no decimal parsing stands between the source
+// and the value.
+__device__ __constant__ const uint32_t kLevelBits[16] = {
+    0xbf800000u, 0xbf3239b1u, 0xbf066b30u, 0xbeca32a0u, 0xbe91a24du, 0xbe3d353fu,
+    0xbdba7871u, 0x00000000u, 0x3da2faffu, 0x3e24cae3u, 0x3e7c04ddu, 0x3ead033au,
+    0x3ee1a4b8u, 0x3f1007abu, 0x3f3913b3u, 0x3f800000u};
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float float2_t __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Two FP32 values -> one dword of two 16-bit values, `lo` in the low half.
+// Both conversions round to nearest even (the wave's default rounding mode),
+// keep subnormals and overflow to infinity.
+template <int DT>
+__device__ __forceinline__ uint32_t pack2(float lo, float hi);
+
+template <>
+__device__ __forceinline__ uint32_t pack2<NF4_FP16>(float lo, float hi) {
+    float2_t v = {lo, hi};
+    half2_t h = __builtin_convertvector(v, half2_t);
+    return __builtin_bit_cast(uint32_t, h);
+}
+
+template <>
+__device__ __forceinline__ uint32_t pack2<NF4_BF16>(float lo, float hi) {
+    float2_t v = {lo, hi};
+    bf16x2_t h = __builtin_convertvector(v, bf16x2_t);
+    return __builtin_bit_cast(uint32_t, h);
+}
+
+template <int DT>
+__device__ __forceinline__ uint16_t narrow1(float v) {
+    return (uint16_t)(pack2<DT>(v, 0.0f) & 0xffffu);
+}
+
+}  // namespace nf4

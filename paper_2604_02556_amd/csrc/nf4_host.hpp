@@ -1,0 +1,31 @@
+// Host-side argument checks and launch bookkeeping shared by the entry points.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/nf4.h"
+
+namespace nf4 {
+
+// hipError_t of the last failed launch on this thread (nf4_last_hip_error).
+extern thread_local int g_last_hip_error;
+
+inline int record_hip(hipError_t e) {
+    if (e == hipSuccess) return NF4_OK;
+    g_last_hip_error = (int)e;
+    return NF4_ERR_HIP;
+}
+
+inline bool aligned(const void* p, uintptr_t a) { return ((uintptr_t)p & (a - 1)) == 0; }
+
+// log2(blocksize) for a power of two in [64, 4096], else -1.
+inline int log2_blocksize(int bs) {
+    for (int s = 6; s <= 12; ++s)
+        if (bs == (1 << s)) return s;
+    return -1;
+}
+
+// Compute units of the current device (queried once per thread; 256 on MI355X).
+int compute_units();
+
+}  // namespace nf4

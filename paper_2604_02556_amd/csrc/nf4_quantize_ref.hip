@@ -1,0 +1,152 @@
+// Reference-quality NF4 quantiser for gfx950: the forward direction of
+// Sec. II-B (block absmax, nearest of the 16 levels), plus this library's
+// second-level quantisation of the absmax array.  Written for exactness, not
+// speed: every FP32 step is the one the definition names, in the same order,
+// so codes and scales are reproducible bit for bit.
+#include "nf4_device.hpp"
+#include "nf4_host.hpp"
+
+namespace nf4 {
+
+constexpr int kQThreads = 256;
+constexpr int kQWaves = kQThreads / kWave;
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+        float o = __shfl_xor(v, m, kWave);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
+// One wave per quantisation block.  Pass 1: absmax.  Pass 2: for every pair of
+// elements the even lane gathers its neighbour's code and writes the byte
+// (element 2j in the high nibble).
+__global__ __launch_bounds__(kQThreads) void quantize_kernel(const float* __restrict__ src, int64_t n,
+                                                             int blocksize, int64_t nb,
+                                                             uint8_t* __restrict__ packed,
+                                                             float* __restrict__ absmax) {
+    __shared__ float lut[16];
+    if (threadIdx.x < 16) lut[threadIdx.x] = __uint_as_float(kLevelBits[threadIdx.x]);
+    __syncthreads();
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t stride = (int64_t)gridDim.x * kQWaves;
+    for (int64_t b = (int64_t)blockIdx.x * kQWaves + (threadIdx.x >> 6); b < nb; b += stride) {
+        const int64_t lo = b * blocksize;
+        const int64_t hi = lo + blocksize < n ? lo + blocksize : n;
+        float a = 0.0f;
+        for (int64_t i = lo + lane; i < hi; i += kWave) {
+            float m = fabsf(src[i]);
+            a = m > a ? m : a;
+        }
+        a = wave_max(a);
+        if (lane == 0) absmax[b] = a;
+        for (int64_t i0 = lo; i0 < hi; i0 += kWave) {      // uniform trip count: shuffles stay converged
+            const int64_t i = i0 + lane;
+            unsigned best = 7;
+            if (i < hi && a != 0.0f) {
+                const float xn = src[i] / a;               // IEEE division
+                float best_d = fabsf(xn - lut[0]);
+                best = 0;
+#pragma unroll
+                for (unsigned k = 1; k < 16; ++k) {
+                    float d = fabsf(xn - lut[k]);
+                    if (d < best_d) { best_d = d; best = k; }   // strict: ties keep the lower index
+                }
+            }
+            const unsigned next = __shfl_down(best, 1, kWave); // code of element i + 1 (7 if absent)
+            if ((lane & 1) == 0 && i < hi) packed[i >> 1] = (uint8_t)((best << 4) | (i + 1 < hi ? next : 7u));
+        }
+    }
+}
+
+// offset = float(sum(absmax) / nb), the sum taken in double in index order by
+// one lane, so that it equals a sequential CPU sum bit for bit.  The wave only
+// helps by staging 1024 values at a time in LDS.
+__global__ __launch_bounds__(kWave) void dq_offset_kernel(const float* __restrict__ absmax, int64_t nb,
+                                                          float* __restrict__ offset,
+                                                          float* __restrict__ code2) {
+    __shared__ float buf[1024];
+    for (int u = threadIdx.x; u < 256; u += kWave) code2[u] = (float)(u - 127) / 127.0f;
+    double sum = 0.0;
+    for (int64_t base = 0; base < nb; base += 1024) {
+        const int64_t left = nb - base;
+        const int cnt = left < 1024 ? (int)left : 1024;
+        __syncthreads();
+        for (int j = threadIdx.x; j < cnt; j += kWave) buf[j] = absmax[base + j];
+        __syncthreads();
+        if (threadIdx.x == 0)
+            for (int j = 0; j < cnt; ++j) sum += (double)buf[j];
+    }
+    if (threadIdx.x == 0) offset[0] = (float)(sum / (double)nb);
+}
+
+// One wave per group of 256 first-level scales.
+__global__ __launch_bounds__(kQThreads) void dq_encode_kernel(const float* __restrict__ absmax, int64_t nb,
+                                                              int64_t ng, const float* __restrict__ offset,
+                                                              uint8_t* __restrict__ q8,
+                                                              float* __restrict__ scale2) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const float off = offset[0];
+    const int64_t stride = (int64_t)gridDim.x * kQWaves;
+    for (int64_t g = (int64_t)blockIdx.x * kQWaves + (threadIdx.x >> 6); g < ng; g += stride) {
+        const int64_t lo = g * 256;
+        const int64_t hi = lo + 256 < nb ? lo + 256 : nb;
+        float s = 0.0f;
+        for (int64_t b = lo + lane; b < hi; b += kWave) {
+            float d = fabsf(absmax[b] - off);
+            s = d > s ? d : s;
+        }
+        s = wave_max(s);
+        if (lane == 0) scale2[g] = s;
+        for (int64_t b = lo + lane; b < hi; b += kWave) {
+            int q = 127;
+            if (s != 0.0f) {
+                const float centred = absmax[b] - off;
+                const float scaled = 127.0f * centred;
+                float r = rintf(scaled / s);               // ties to even
+                r = r < -127.0f ? -127.0f : r;
+                r = r > 127.0f ? 127.0f : r;
+                q = 127 + (int)r;
+            }
+            q8[b] = (uint8_t)q;
+        }
+    }
+}
+
+}  // namespace nf4
+
+extern "C" int nf4_quantize_ref(const float* src, int64_t n, int blocksize, uint8_t* packed, float* absmax,
+                                uint8_t* absmax_q8, float* scale2, float* offset, float* code2,
+                                void* stream) {
+    using namespace nf4;
+    if (n < 0) return NF4_ERR_SIZE;
+    if (log2_blocksize(blocksize) < 0) return NF4_ERR_BLOCKSIZE;
+    if (n == 0) return NF4_OK;
+    if (!src || !packed || !absmax) return NF4_ERR_NULL;
+    const bool dq = absmax_q8 != nullptr;
+    if (dq && (!scale2 || !offset || !code2)) return NF4_ERR_NULL;
+    if (!aligned(src, 4) || !aligned(absmax, 4)) return NF4_ERR_ALIGN;
+    if (dq && (!aligned(scale2, 4) || !aligned(offset, 4) || !aligned(code2, 4))) return NF4_ERR_ALIGN;
+
+    hipStream_t s = (hipStream_t)stream;
+    const int64_t nb = (n + blocksize - 1) / blocksize;
+    const int64_t cap = (int64_t)compute_units() * 16;
+    int64_t groups = (nb + kQWaves - 1) / kQWaves;
+    groups = groups < cap ? groups : cap;
+    hipLaunchKernelGGL(quantize_kernel, dim3((unsigned)groups), dim3(kQThreads), 0, s, src, n, blocksize, nb,
+                       packed, absmax);
+    int rc = record_hip(hipGetLastError());
+    if (rc != NF4_OK || !dq) return rc;
+
+    const int64_t ng = (nb + 255) / 256;
+    hipLaunchKernelGGL(dq_offset_kernel, dim3(1), dim3(kWave), 0, s, (const float*)absmax, nb, offset, code2);
+    rc = record_hip(hipGetLastError());
+    if (rc != NF4_OK) return rc;
+    int64_t g2 = (ng + kQWaves - 1) / kQWaves;
+    g2 = g2 < cap ? g2 : cap;
+    hipLaunchKernelGGL(dq_encode_kernel, dim3((unsigned)g2), dim3(kQThreads), 0, s, (const float*)absmax, nb, ng,
+                       (const float*)offset, absmax_q8, scale2);
+    return record_hip(hipGetLastError());
+}

@@ -1,0 +1,115 @@
+"""Host-side checks of the C-ABI: the library loads, exports what include/nf4.h
+declares, and rejects bad arguments before launching anything (so these run
+without a GPU)."""
+import os
+import re
+
+import pytest
+
+from paper_2604_02556_amd import binding, build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "nf4.h")
+
+OK, E_NULL, E_SIZE, E_BS, E_DT, E_ALIGN, E_SHAPE, E_HIP = range(8)
+P = 4096          # a well-aligned fake device address; never dereferenced on these paths
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(build.lib_path()):
+        build.build()
+    return binding.lib()
+
+
+def declared_functions():
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    return re.findall(r"\b(nf4_[a-z0-9_]+)\s*\(", text)
+
+
+def test_every_declared_symbol_is_exported(L):
+    names = declared_functions()
+    assert set(names) >= {"nf4_dequantize", "nf4_dequantize_dq", "nf4_dequant_gemv", "nf4_quantize_ref",
+                          "nf4_last_hip_error", "nf4_status_string"}
+    for name in names:
+        assert hasattr(L, name), name
+
+
+def test_status_strings(L):
+    names = ["NF4_OK", "NF4_ERR_NULL", "NF4_ERR_SIZE", "NF4_ERR_BLOCKSIZE", "NF4_ERR_DTYPE", "NF4_ERR_ALIGN",
+             "NF4_ERR_SHAPE", "NF4_ERR_HIP"]
+    for code, name in enumerate(names):
+        assert binding.status_string(code) == name
+    assert binding.status_string(99) == "NF4_ERR_UNKNOWN"
+    assert L.nf4_last_hip_error() == 0
+
+
+def test_dequantize_argument_checks(L):
+    f = L.nf4_dequantize
+    assert f(P, P, 64, -1, P, 0, None) == E_SIZE
+    for bs in (0, 32, 63, 96, 8192, -64):
+        assert f(P, P, bs, 10, P, 0, None) == E_BS
+    assert f(P, P, 64, 10, P, 2, None) == E_DT
+    assert f(None, None, 64, 0, None, 0, None) == OK            # empty tensor: nothing to do
+    assert f(None, P, 64, 10, P, 0, None) == E_NULL
+    assert f(P, None, 64, 10, P, 0, None) == E_NULL
+    assert f(P, P, 64, 10, None, 1, None) == E_NULL
+    assert f(P + 8, P, 64, 10, P, 0, None) == E_ALIGN
+    assert f(P, P + 2, 64, 10, P, 0, None) == E_ALIGN
+    assert f(P, P, 64, 10, P + 2, 0, None) == E_ALIGN
+
+
+def test_dequantize_dq_argument_checks(L):
+    f = L.nf4_dequantize_dq
+    assert f(P, P, P, P, P, 64, -5, P, 0, None) == E_SIZE
+    assert f(P, P, P, P, P, 100, 5, P, 0, None) == E_BS
+    assert f(P, P, P, P, P, 64, 5, P, 7, None) == E_DT
+    assert f(None, None, None, None, None, 64, 0, None, 1, None) == OK
+    for hole in range(5):
+        args = [P] * 5
+        args[hole] = None
+        assert f(*args, 64, 5, P, 0, None) == E_NULL
+    assert f(P, P + 1, P + 2, P, P, 64, 5, P, 0, None) == E_ALIGN     # q8 may be odd, scale2 may not
+    assert f(P, P + 1, P, P, P, 64, 5, P + 4, 0, None) == E_ALIGN
+
+
+def test_gemv_argument_checks(L):
+    f = L.nf4_dequant_gemv
+    a = [P] * 5
+    assert f(*a, 64, -1, 64, P, 1, P, None) == E_SIZE
+    assert f(*a, 48, 4, 64, P, 1, P, None) == E_BS
+    assert f(*a, 64, 4, 64, P, 0, P, None) == E_SHAPE
+    assert f(*a, 64, 4, 64, P, 17, P, None) == E_SHAPE
+    assert f(*a, 64, 4, 96, P, 1, P, None) == E_SHAPE
+    assert f(*a, 64, 4, 0, P, 1, P, None) == E_SHAPE
+    assert f(*a, 64, 0, 64, P, 1, P, None) == OK
+    assert f(*a, 64, 4, 64, None, 1, P, None) == E_NULL
+    assert f(*a, 64, 4, 64, P, 1, None, None) == E_NULL
+    assert f(*a, 64, 4, 64, P + 2, 1, P, None) == E_ALIGN
+    assert f(*a, 64, 4, 64, P, 1, P + 1, None) == E_ALIGN
+
+
+def test_quantize_ref_argument_checks(L):
+    f = L.nf4_quantize_ref
+    assert f(P, -1, 64, P, P, None, None, None, None, None) == E_SIZE
+    assert f(P, 5, 65, P, P, None, None, None, None, None) == E_BS
+    assert f(None, 0, 64, None, None, None, None, None, None, None) == OK
+    assert f(None, 5, 64, P, P, None, None, None, None, None) == E_NULL
+    assert f(P, 5, 64, P, None, None, None, None, None, None) == E_NULL
+    assert f(P, 5, 64, P, P, P, None, P, P, None) == E_NULL             # DQ wants all four outputs
+    assert f(P + 2, 5, 64, P, P, None, None, None, None, None) == E_ALIGN
+
+
+def test_binding_raises_with_the_status_name():
+    with pytest.raises(binding.NF4Error, match="NF4_ERR_BLOCKSIZE"):
+        binding._check(E_BS)
+
+
+def test_product_code_never_touches_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2604_02556_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for name in files:
+            if name.endswith((".py", ".hip", ".hpp", ".h")):
+                text = open(os.path.join(dirpath, name)).read()
+                for needle in ("import oracle", "from oracle", "nf4_oracle", "nf4o_"):
+                    assert needle not in text, (needle, os.path.join(dirpath, name))

@@ -1,0 +1,139 @@
+"""GPU parity: libnf4's dequantisation (through the C-ABI) against the CPU oracle,
+bit for bit, on seeded inputs spanning several wave tiles and ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2604_02556_amd import synth
+from gpu_util import (dequantize_dq_gpu, dequantize_gpu, guard_intact, mismatches)
+
+pytestmark = pytest.mark.gpu
+
+DT = {"fp16": (torch.float16, oracle.FP16), "bf16": (torch.bfloat16, oracle.BF16)}
+
+
+@pytest.mark.parametrize("dt", ["fp16", "bf16"])
+def test_config0_1024x1024(dt):
+    tdt, odt = DT[dt]
+    n = 1024 * 1024
+    w = synth.gaussian_weights(n, 0.02, seed=0)
+    packed, absmax = oracle.quantize(w)
+    want = oracle.dequantize(packed, absmax, n, out_dtype=odt)
+    whole, got = dequantize_gpu(packed, absmax, n, tdt)
+    assert mismatches(got, want, dt == "bf16") == 0
+    assert guard_intact(whole, n)
+
+
+@pytest.mark.parametrize("dt", ["fp16", "bf16"])
+def test_exhaustive_byte_values(dt):
+    tdt, odt = DT[dt]
+    packed = np.tile(np.arange(256, dtype=np.uint8), 20)            # 10240 elements: > 2 wave tiles + tail
+    n = packed.size * 2
+    absmax = synth.positive_scales(n // 64, seed=3, lo=0.5, hi=2.0)
+    absmax[:8] = 1.0
+    whole, got = dequantize_gpu(packed, absmax, n, tdt)
+    assert np.array_equal(got, oracle.dequantize(packed, absmax, n, out_dtype=odt))
+    assert guard_intact(whole, n)
+
+
+@pytest.mark.parametrize("dt", ["fp16", "bf16"])
+def test_extreme_scales_subnormal_overflow_nan(dt):
+    tdt, odt = DT[dt]
+    specials = np.array([0.0, 2.0**-20, 2.0**-24, 2.0**-25, 3e-8, 6.1e-5, 65504.0, 65520.0, 7e4, 1e30, 3.3e38,
+                         np.inf, 1e-40, 1e-45, -1.0, 2.0**-14 * 1.0009765], dtype=np.float32)
+    absmax = np.concatenate([specials, synth.positive_scales(4096 - specials.size, seed=5, lo=1e-9, hi=1e6)])
+    n = absmax.size * 64
+    packed = synth.random_codes(n // 2, seed=6)
+    whole, got = dequantize_gpu(packed, absmax, n, tdt)
+    want = oracle.dequantize(packed, absmax, n, out_dtype=odt)
+    assert mismatches(got, want, dt == "bf16") == 0
+    assert guard_intact(whole, n)
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 63, 64, 65, 127, 2047, 2048, 2049, 8191, 8192 + 33, 1_000_003])
+@pytest.mark.parametrize("dt", ["fp16", "bf16"])
+def test_ragged_sizes_with_guard(n, dt):
+    tdt, odt = DT[dt]
+    packed = synth.random_codes((n + 1) // 2, seed=100 + n % 97)
+    absmax = synth.positive_scales(oracle.nblocks(n), seed=200 + n % 89)
+    whole, got = dequantize_gpu(packed, absmax, n, tdt)
+    assert np.array_equal(got, oracle.dequantize(packed, absmax, n, out_dtype=odt))
+    assert guard_intact(whole, n)
+
+
+def test_empty_tensor_is_a_no_op():
+    whole, got = dequantize_gpu(np.zeros(0, np.uint8), np.zeros(0, np.float32), 0, torch.float16)
+    assert got.size == 0 and guard_intact(whole, 0)
+
+
+@pytest.mark.parametrize("blocksize", [128, 256, 1024, 4096])
+def test_other_blocksizes(blocksize):
+    n = 3 * 8192 + 4096 + 77
+    w = synth.gaussian_weights(n, 0.02, seed=blocksize)
+    packed, absmax = oracle.quantize(w, blocksize)
+    whole, got = dequantize_gpu(packed, absmax, n, torch.float16, blocksize)
+    assert np.array_equal(got, oracle.dequantize(packed, absmax, n, blocksize))
+    assert guard_intact(whole, n)
+
+
+def test_qwen_k_projection_with_outliers_full_compare():
+    n = synth.numel(synth.QWEN3_32B["k"])
+    w = synth.gaussian_weights(n, synth.QWEN3_32B_SIGMA, seed=1001, outlier_p=0.001)
+    packed, absmax = oracle.quantize(w)
+    whole, got = dequantize_gpu(packed, absmax, n, torch.float16)
+    assert np.array_equal(got, oracle.dequantize(packed, absmax, n))
+    assert guard_intact(whole, n)
+
+
+# ------------------------------------------------------------ double quant
+
+def _ulp_distance(a_bits, b_bits):
+    def key(b):
+        b = b.astype(np.int32)
+        return np.where(b & 0x8000, -(b & 0x7FFF), b & 0x7FFF)
+    return np.abs(key(a_bits) - key(b_bits))
+
+
+@pytest.mark.parametrize("dt", ["bf16", "fp16"])
+@pytest.mark.parametrize("n", [1, 63, 65, 16384 * 3 + 640, 1_000_003])
+def test_double_quant_ragged(n, dt):
+    tdt, odt = DT[dt]
+    w = synth.gaussian_weights(n, 0.02, seed=2000 + n % 101)
+    packed, absmax = oracle.quantize(w)
+    q8, s2, off, c2 = oracle.dq_encode(absmax)
+    want = oracle.dequantize_dq(packed, q8, s2, off, c2, n, out_dtype=odt)
+    whole, got = dequantize_dq_gpu(packed, q8, s2, off, c2, n, tdt)
+    bad = mismatches(got, want, dt == "bf16")
+    ulp = int(_ulp_distance(got, want).max())
+    print(f"dq {dt} n={n}: mismatches={bad} max_ulp={ulp}")
+    assert ulp <= 1                    # the stated bar
+    assert bad == 0                    # what unfused mul/add actually delivers
+    assert guard_intact(whole, n)
+
+
+def test_double_quant_gemma_k_projection_bf16_full_compare():
+    n = synth.numel(synth.GEMMA_27B["k"])
+    w = synth.gaussian_weights(n, synth.GEMMA_27B_SIGMA, seed=2001)
+    packed, absmax = oracle.quantize(w)
+    q8, s2, off, c2 = oracle.dq_encode(absmax)
+    want = oracle.dequantize_dq(packed, q8, s2, off, c2, n, out_dtype=oracle.BF16)
+    whole, got = dequantize_dq_gpu(packed, q8, s2, off, c2, n, torch.bfloat16)
+    diff = int((got != want).sum())
+    to_f32 = lambda b: (b.astype(np.uint32) << 16).view(np.float32)
+    print(f"gemma k dq bf16: mismatches={diff} max_abs_err={np.abs(to_f32(got) - to_f32(want)).max():.3e}")
+    assert diff == 0 and guard_intact(whole, n)
+
+
+def test_double_quant_arbitrary_code_map_and_negative_scales():
+    n = 64 * 256 * 3 + 64 * 5
+    nb = n // 64
+    rng = np.random.Generator(np.random.PCG64(77))
+    code2 = (np.linspace(-1, 1, 256) ** 3).astype(np.float32)
+    q8 = rng.integers(0, 256, nb, dtype=np.uint8)
+    s2 = np.array([0.3, -0.7, 1e-4, 2.5], np.float32)
+    off = np.array([0.011], np.float32)
+    packed = synth.random_codes(n // 2, seed=78)
+    want = oracle.dequantize_dq(packed, q8, s2, off, code2, n, out_dtype=oracle.FP16)
+    whole, got = dequantize_dq_gpu(packed, q8, s2, off, code2, n, torch.float16)
+    assert np.array_equal(got, want) and guard_intact(whole, n)

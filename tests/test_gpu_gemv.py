@@ -1,0 +1,78 @@
+"""GPU parity: the fused dequantise + GEMV against the double-precision oracle.
+
+Tolerance (the summation order differs, so this is not bit-exact): per element
+|y - y_ref| <= 1e-2 * |y_ref| + 1e-2 * rms(y_ref).  The fp16 rounding of y
+alone is 2^-11 relative; FP32 accumulation over K <= 28672 terms adds about
+K * 2^-24 relative to the sum of |terms|, far inside the bar."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2604_02556_amd import binding as nf4
+from paper_2604_02556_amd import synth
+from gpu_util import dev
+
+pytestmark = pytest.mark.gpu
+
+
+def make_case(N, K, seed, sigma=0.015):
+    w = synth.gaussian_weights(N * K, sigma, seed)
+    p, a = oracle.quantize(w)
+    q8, s2, off, c2 = oracle.dq_encode(a)
+    return p, q8, s2, off, c2
+
+
+def gemv_gpu(case, N, K, x):
+    p, q8, s2, off, c2 = case
+    B = x.shape[0]
+    y = torch.full((B, N), float("nan"), dtype=torch.float16, device="cuda")
+    nf4.nf4_dequant_gemv(dev(p), dev(q8), dev(s2), dev(off), dev(c2), 64, N, K, dev(x), B, y)
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+def within_bar(y, ref):
+    rms = np.sqrt(np.mean(ref ** 2))
+    return np.all(np.abs(y.astype(np.float64) - ref) <= 1e-2 * np.abs(ref) + 1e-2 * rms)
+
+
+@pytest.mark.parametrize("B", [1, 2, 3, 4, 5, 8, 11, 16])
+@pytest.mark.parametrize("N,K", [(37, 256), (64, 2048 + 512), (9, 8192), (130, 64)])
+def test_small_shapes_all_batches(N, K, B):
+    case = make_case(N, K, seed=N * 7 + K)
+    x = synth.activations_fp16(B, K, seed=B)
+    _, ref = oracle.dequant_gemv(*case, N, K, x.view(np.uint16))
+    y = gemv_gpu(case, N, K, x)
+    assert within_bar(y, ref)
+    err = np.abs(y - ref).max() / np.abs(ref).max()
+    assert err < 2e-3, err
+
+
+def test_unit_vectors_reproduce_columns_of_dequantized_w():
+    N, K = 40, 512
+    case = make_case(N, K, seed=5)
+    w = oracle.dequantize_dq(*case, N * K, out_dtype=oracle.FP32).reshape(N, K)
+    ks = [0, 1, 7, 8, 63, 64, 255, 256, 511]
+    for k0 in range(0, len(ks), 4):
+        chunk = ks[k0:k0 + 4]
+        x = np.zeros((len(chunk), K), np.float16)
+        for b, k in enumerate(chunk):
+            x[b, k] = 1.0
+        y = gemv_gpu(case, N, K, x)
+        want = w[:, chunk].T.astype(np.float16)          # one product, one rounding: exact
+        assert np.array_equal(y.view(np.uint16), want.view(np.uint16))
+
+
+def test_zero_activations_and_all_ones_weights():
+    N, K = 16, 1024
+    case = make_case(N, K, seed=6)
+    y0 = gemv_gpu(case, N, K, np.zeros((2, K), np.float16))
+    assert np.all(y0 == 0)
+    c2 = ((np.arange(256) - 127) / 127).astype(np.float32)
+    ones = (np.full(N * K // 2, 0xFF, np.uint8), np.full(N * K // 64, 254, np.uint8), np.ones(1, np.float32),
+            np.zeros(1, np.float32), c2)
+    x = synth.activations_fp16(4, K, seed=7)
+    y = gemv_gpu(ones, N, K, x)
+    want = x.astype(np.float64).sum(axis=1, keepdims=True).repeat(N, 1)
+    assert np.allclose(y, want, rtol=2e-3, atol=2e-2)

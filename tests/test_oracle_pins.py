@@ -355,3 +355,11 @@ def test_gemv_unit_vector_zero_and_all_ones_cases():
     _, ys = oracle.dequant_gemv(ones_p, np.full(nb, 254, np.uint8), np.ones(1, np.float32),
                                 np.zeros(1, np.float32), c2, N, K, x.view(np.uint16))
     assert np.allclose(ys, x.astype(np.float64).sum(axis=1, keepdims=True).repeat(N, 1), rtol=0, atol=1e-12)
+
+
+def test_gemv_row_range_is_a_slice_of_the_whole():
+    N, K, B = 24, 256, 3
+    p, q8, s2, off, c2, x = _small_gemv_case(N, K, B)
+    yb, y64 = oracle.dequant_gemv(p, q8, s2, off, c2, N, K, x.view(np.uint16))
+    rb, r64 = oracle.dequant_gemv_rows(p, q8, s2, off, c2, N, K, x.view(np.uint16), 5, 7)
+    assert np.array_equal(rb, yb[:, 5:12]) and np.array_equal(r64, y64[:, 5:12])
