@@ -43,8 +43,12 @@ __device__ __forceinline__ uint32_t pack2<NF4_BF16>(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, h);
 }
 
+// One value.  The empty asm pins `v` as a finished FP32 result: without it the
+// compiler folds a preceding multiply into a mixed-precision multiply-add with
+// a +0 addend, which turns a product of -0 into +0.
 template <int DT>
 __device__ __forceinline__ uint16_t narrow1(float v) {
+    asm volatile("" : "+v"(v));
     return (uint16_t)(pack2<DT>(v, 0.0f) & 0xffffu);
 }
 

@@ -363,3 +363,12 @@ def test_gemv_row_range_is_a_slice_of_the_whole():
     yb, y64 = oracle.dequant_gemv(p, q8, s2, off, c2, N, K, x.view(np.uint16))
     rb, r64 = oracle.dequant_gemv_rows(p, q8, s2, off, c2, N, K, x.view(np.uint16), 5, 7)
     assert np.array_equal(rb, yb[:, 5:12]) and np.array_equal(r64, y64[:, 5:12])
+
+
+def test_zero_level_times_negative_scale_is_negative_zero():
+    # IEEE: (+0) * (negative) = -0; the multiply is a lone FP32 product, never "+ 0"
+    packed = np.full(32, 0x77, np.uint8)
+    out = oracle.dequantize(packed, np.array([-2.0], np.float32), 64)
+    assert np.all(out == 0x8000)
+    outb = oracle.dequantize(packed, np.array([-2.0], np.float32), 64, out_dtype=oracle.BF16)
+    assert np.all(outb == 0x8000)
