@@ -48,6 +48,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true")
     ap.add_argument("--per-shape", action="store_true", help="also time each tensor shape on its own")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="finish with one plain 256 MiB -> 256 MiB device copy (calibrates rocprofv3 byte counters)")
     return ap.parse_args()
 
 
@@ -156,6 +158,12 @@ def main():
         "roofline": roofline,
     }
 
+    if args.calibration_copy:
+        a = torch.empty(256 << 20, dtype=torch.uint8, device=dev).fill_(3)
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        b.copy_(a)                                      # reads 268435456 bytes, writes 268435456 bytes
+        torch.cuda.synchronize()
     if args.per_shape:
         result["per_shape"] = per_shape(torch, nf4, stream, tensors, names, out)
     if not args.no_extra:

@@ -19,6 +19,10 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-ffp-contract=off", "-fP
          "-Wall", "-Wno-unused-command-line-argument"]
 
 
+STUDY_SRC = os.path.join(HERE, "study", "codebook_study.hip")
+STUDY_BIN = os.path.join(HERE, "study", "codebook_study")
+
+
 def lib_path() -> str:
     return LIB
 
@@ -44,7 +48,20 @@ def build(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + out)
     if verbose and out.strip():
         print(out)
+    build_study(verbose)
     return LIB
+
+
+def build_study(verbose: bool = False) -> str:
+    """The codebook-placement study: a standalone measurement program (not part of libnf4)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc] + [f for f in FLAGS if f != "-fPIC"] + ["-o", STUDY_BIN, STUDY_SRC]
+    if verbose:
+        print(" ".join(cmd))
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout)
+    return STUDY_BIN
 
 
 if __name__ == "__main__":

@@ -18,11 +18,17 @@
 //     address order -- rather than a persistent grid-stride loop: in-order
 //     dispatch keeps the write frontier compact and measured 15-20 % faster
 //     than 2048 resident workgroups striding through the tensor;
-//   * the 16 levels live in a VGPR (lane l holds level l mod 16, built from
-//     instruction literals) and are looked up with ds_bpermute_b32: the LDS
-//     crossbar without LDS storage, so there is no table initialisation, no
-//     memory read and no barrier before the first lookup, and no bank conflict
-//     is possible;
+//   * the 16 levels sit in 64 bytes of LDS, written once per wave by lanes
+//     0..15 from instruction literals (no memory read, and with single-wave
+//     workgroups no barrier).  16 consecutive dwords fall in 16 distinct banks
+//     and lanes that pick the same level are served by broadcast, so the
+//     lookup cannot conflict (SQ_LDS_BANK_CONFLICT = 0).  Measured against a
+//     VGPR table read with ds_bpermute_b32, a 256-entry byte-pair LDS table, a
+//     table re-read from memory and a pure select chain: the kernel time of the
+//     first three is equal within 2 % (the path is HBM-bound), the plain LDS
+//     table keeps the LDS pipe busy for about half as many cycles as
+//     ds_bpermute, the byte-pair table conflicts, and the last two halve the
+//     throughput;
 //   * nibble split is a shift and a mask (Sec. IV-D), the product is one FP32
 //     multiply, two products are narrowed and packed per dword by the packed
 //     round-to-nearest-even converts, eight values per 128-bit store;
@@ -54,32 +60,26 @@ __device__ __forceinline__ void wave_lds_fence() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// level[lane mod 16] as a bit pattern, selected from instruction literals.
-__device__ __forceinline__ int lane_level(int lane) {
-    const int i = lane & 15;
+// level[i] as a bit pattern, selected from instruction literals.
+__device__ __forceinline__ uint32_t level_literal(uint32_t i) {
     uint32_t v = 0xbf800000u;
     v = i == 1 ? 0xbf3239b1u : v;  v = i == 2 ? 0xbf066b30u : v;  v = i == 3 ? 0xbeca32a0u : v;
     v = i == 4 ? 0xbe91a24du : v;  v = i == 5 ? 0xbe3d353fu : v;  v = i == 6 ? 0xbdba7871u : v;
     v = i == 7 ? 0x00000000u : v;  v = i == 8 ? 0x3da2faffu : v;  v = i == 9 ? 0x3e24cae3u : v;
     v = i == 10 ? 0x3e7c04ddu : v; v = i == 11 ? 0x3ead033au : v; v = i == 12 ? 0x3ee1a4b8u : v;
     v = i == 13 ? 0x3f1007abu : v; v = i == 14 ? 0x3f3913b3u : v; v = i == 15 ? 0x3f800000u : v;
-    return (int)v;
-}
-
-// level[code] for a per-lane code: read lane `code` of the table register.
-__device__ __forceinline__ float lookup(int table_reg, uint32_t code) {
-    return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((int)(code << 2), table_reg));
+    return v;
 }
 
 // Eight codes of one dword -> eight scaled 16-bit values.  Byte j of the dword
 // holds element 2j in its high nibble and element 2j+1 in its low nibble.
 template <int DT>
-__device__ __forceinline__ u32x4 expand8(uint32_t q, float s, int table_reg) {
+__device__ __forceinline__ u32x4 expand8(uint32_t q, float s, const float* lut) {
     u32x4 r;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        const float hi = lookup(table_reg, (q >> (8 * j + 4)) & 15u) * s;
-        const float lo = lookup(table_reg, (q >> (8 * j)) & 15u) * s;
+        const float hi = lut[(q >> (8 * j + 4)) & 15u] * s;
+        const float lo = lut[(q >> (8 * j)) & 15u] * s;
         r[j] = pack2<DT>(hi, lo);
     }
     return r;
@@ -97,10 +97,11 @@ __global__ __launch_bounds__(kWave) void dequant_kernel(const uint8_t* __restric
                                                         int log2_bs, int64_t n, int64_t tiles,
                                                         uint16_t* __restrict__ out) {
     __shared__ uint32_t stage[kTileBytes / 4];
+    __shared__ float lut[16];
     const int lane = threadIdx.x;
     const int64_t t = blockIdx.x;
-    const int table_reg = lane_level(lane);
     const float offset = DQ ? sa.offset[0] : 0.0f;
+    if (lane < 16) lut[lane] = __uint_as_float(level_literal(lane));   // ordered by the fence below
 
     if (t < tiles) {
         const int64_t e0 = t * kTileElems;
@@ -131,14 +132,13 @@ __global__ __launch_bounds__(kWave) void dequant_kernel(const uint8_t* __restric
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const uint32_t q = stage[64 * k + lane];
-            const u32x4 v = expand8<DT>(q, s[k], table_reg);
+            const u32x4 v = expand8<DT>(q, s[k], lut);
             __builtin_nontemporal_store(v, (u32x4*)(out_tile + 512 * k + 8 * lane));
         }
     } else {
         // Ragged end: everything after the last full tile, one byte (two
         // elements of the same block) per lane, every access predicated on n.
-        // The loop is wave-uniform and the lookups sit outside the predicated
-        // parts, so the lanes holding the table are active whenever it is read.
+        wave_lds_fence();
         const int64_t nbytes = (n + 1) >> 1;
         for (int64_t base = tiles * kTileBytes; base < nbytes; base += kWave) {
             const int64_t b = base + lane;
@@ -150,8 +150,8 @@ __global__ __launch_bounds__(kWave) void dequant_kernel(const uint8_t* __restric
                 q = packed[b];
                 sc = DQ ? dq_scale(sa, offset, i >> log2_bs) : sa.absmax[i >> log2_bs];
             }
-            const float hi = lookup(table_reg, q >> 4) * sc;
-            const float lo = lookup(table_reg, q & 15u) * sc;
+            const float hi = lut[q >> 4] * sc;
+            const float lo = lut[q & 15u] * sc;
             if (live) {
                 out[i] = narrow1<DT>(hi);
                 if (i + 1 < n) out[i + 1] = narrow1<DT>(lo);
