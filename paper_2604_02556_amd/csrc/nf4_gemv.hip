@@ -4,137 +4,296 @@
 // handful of tokens that temporary is the dominant traffic, so it is never
 // written here).
 //
-// Not a dense contraction at these batch sizes, so no MFMA: FP32 FMAs, wave64
-// reductions.  Layout of the work:
-//   * a workgroup of 4 waves owns kRows consecutive rows of W; wave w takes the
-//     k-slices w, w+4, ... so the four waves stream disjoint parts of the same
-//     rows and their partial sums meet in LDS in a fixed order (deterministic);
-//   * inside a slice lane l owns CH consecutive dwords of codes (8*CH elements,
-//     always inside one quantisation block), loads them with one 128-bit (CH=4)
-//     or 32-bit (CH=1) load per row, contiguous across the wave;
-//   * its 8*CH activations per token are converted to FP32 once per slice and
-//     reused for all kRows rows;
+// Not a dense contraction at these batch sizes, so no MFMA: FP32 FMAs and
+// wave64 DPP reductions.  Layout of the work:
+//   * one wave (a single-wave workgroup, one-shot grid) owns R consecutive rows
+//     of W over the whole of K, so no partial sums ever leave the wave and the
+//     summation order is fixed (deterministic results);
+//   * per step lane l owns CH consecutive dwords of codes of each row (8*CH
+//     elements, always inside one quantisation block): one 128-bit (CH=4) or
+//     32-bit (CH=1) load per row, contiguous across the wave.  The loads of
+//     step i+1 are issued before the arithmetic of step i;
+//   * its 8*CH activations per token stay FP16 in registers and enter the FP32
+//     multiply-add directly (mixed-precision FMA), reused for all R rows;
+//   * levels come from a 16-entry LDS table written from literals (no bank
+//     conflicts, see nf4_dequant.hip); the double-quantisation map code2 sits
+//     in 1 KiB of LDS;
 //   * the block scale is applied once per lane chunk (sum of level*x first,
-//     then one multiply-add by the scale), not once per element.
+//     then one multiply-add by the scale), not once per element;
+//   * addresses of the level table are taken four at a time: two masked copies
+//     of a code dword hold code*4 in each byte, one bit-field extract each;
+//   * each accumulator is reduced across the wave with six DPP adds.
 #include "nf4_device.hpp"
 #include "nf4_host.hpp"
 
 namespace nf4 {
 
-constexpr int kGThreads = 256;
-constexpr int kGWaves = kGThreads / kWave;
-constexpr int kRows = 4;
-
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 
-template <int B, int CH>
-__global__ __launch_bounds__(kGThreads) void gemv_kernel(const uint8_t* __restrict__ packed,
-                                                         const uint8_t* __restrict__ q8,
-                                                         const float* __restrict__ scale2,
-                                                         const float* __restrict__ offset_p,
-                                                         const float* __restrict__ code2, int log2_bs,
-                                                         int64_t N, int64_t K,
-                                                         const _Float16* __restrict__ x,
-                                                         _Float16* __restrict__ y) {
-    constexpr int E = 8 * CH;                 // elements per lane per slice
-    constexpr int kSlice = E * kWave;         // elements per wave per slice
-    __shared__ float lut[16];
-    __shared__ float code2_lds[256];
-    __shared__ float partial[kGWaves][kRows][B];
+__device__ __forceinline__ uint32_t gemv_level_literal(uint32_t i) {
+    uint32_t v = 0xbf800000u;
+    v = i == 1 ? 0xbf3239b1u : v;  v = i == 2 ? 0xbf066b30u : v;  v = i == 3 ? 0xbeca32a0u : v;
+    v = i == 4 ? 0xbe91a24du : v;  v = i == 5 ? 0xbe3d353fu : v;  v = i == 6 ? 0xbdba7871u : v;
+    v = i == 7 ? 0x00000000u : v;  v = i == 8 ? 0x3da2faffu : v;  v = i == 9 ? 0x3e24cae3u : v;
+    v = i == 10 ? 0x3e7c04ddu : v; v = i == 11 ? 0x3ead033au : v; v = i == 12 ? 0x3ee1a4b8u : v;
+    v = i == 13 ? 0x3f1007abu : v; v = i == 14 ? 0x3f3913b3u : v; v = i == 15 ? 0x3f800000u : v;
+    return v;
+}
 
-    if (threadIdx.x < 16) lut[threadIdx.x] = __uint_as_float(kLevelBits[threadIdx.x]);
-    code2_lds[threadIdx.x] = code2[threadIdx.x];
-    __syncthreads();
-    const float offset = offset_p[0];
+__device__ __forceinline__ void gemv_lds_fence() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
 
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t r0 = (int64_t)blockIdx.x * kRows;
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_add(float v) {
+    const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xF, false);
+    return v + __builtin_bit_cast(float, moved);
+}
 
-    float acc[kRows][B];
-#pragma unroll
-    for (int r = 0; r < kRows; ++r)
-#pragma unroll
-        for (int b = 0; b < B; ++b) acc[r][b] = 0.0f;
+// Sum over the 64 lanes; the total lands in lane 63.
+__device__ __forceinline__ float wave_sum_to_lane63(float v) {
+    v = dpp_add<0xB1, 0xF>(v);    // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E, 0xF>(v);    // quad_perm [2,3,0,1]
+    v = dpp_add<0x114, 0xF>(v);   // row_shr:4
+    v = dpp_add<0x118, 0xF>(v);   // row_shr:8   -> lane 15 of each row holds the row sum
+    v = dpp_add<0x142, 0xA>(v);   // row_bcast:15 into rows 1 and 3
+    v = dpp_add<0x143, 0xC>(v);   // row_bcast:31 into rows 2 and 3
+    return v;
+}
 
-    for (int64_t k0 = (int64_t)wave * kSlice; k0 < K; k0 += (int64_t)kGWaves * kSlice) {
-        const int64_t k = k0 + (int64_t)lane * E;
-        if (k < K) {                                   // K % E == 0: a lane chunk is all in or all out
-            float xf[B][E];
+// One step's worth of operands for one lane.
+template <int B, int CH, int R>
+struct StepRegs {
+    uint32_t q[R][CH];      // codes
+    half8_t xh[B][CH];      // activations, still FP16
+    uint32_t q8[R];         // 8-bit scale codes
+    float s2[R];            // second-level scales
+};
+
+// Wave-uniform row bases, computed once: codes and scale codes of the rows'
+// first elements.  K is a multiple of the blocksize, so a row starts a block.
+template <int R>
+struct RowBases {
+    const uint8_t* codes[R];   // packed + row_start / 2
+    const uint8_t* q8[R];      // q8 + row_start / blocksize
+    uint32_t blk_lo[R];        // (row_start / blocksize) mod 256
+    const float* s2[R];        // scale2 + (row_start / blocksize) / 256
+};
+
+// Loads of one step.  `k0` (first element of the step) is wave-uniform, so every
+// address is a scalar base plus a 32-bit per-lane offset.
+// FULL: every lane chunk is inside K and all R rows exist, so nothing is predicated.
+template <int B, int CH, int R, bool FULL>
+__device__ __forceinline__ void load_step(StepRegs<B, CH, R>& g, const RowBases<R>& rb,
+                                          const _Float16* __restrict__ x, int log2_bs, int64_t K, int rows,
+                                          int64_t k0, int lane) {
+    constexpr int E = 8 * CH;
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    const uint32_t le = (uint32_t)lane * E;                        // element offset of this lane in the step
+    const bool live = FULL || k0 + le < K;
+    if (live) {
+        // block index inside the row = (k0 + le) >> log2_bs: uniform part + small per-lane part
+        const int64_t kb = k0 >> log2_bs;
+        const uint32_t vb = ((uint32_t)(k0 & ((1 << log2_bs) - 1)) + le) >> log2_bs;
 #pragma unroll
-            for (int b = 0; b < B; ++b)
-#pragma unroll
-                for (int c = 0; c < CH; ++c) {
-                    const half8_t h = *(const half8_t*)(x + (int64_t)b * K + k + 8 * c);
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) xf[b][8 * c + j] = (float)h[j];
-                }
-#pragma unroll
-            for (int r = 0; r < kRows; ++r) {
-                if (r0 + r < N) {
-                    const int64_t e = (r0 + r) * K + k;            // flat element index
-                    uint32_t q[CH];
-                    if constexpr (CH == 4) {
-                        const u32x4 v = *(const u32x4*)(packed + (e >> 1));
-                        q[0] = v[0]; q[1] = v[1]; q[2] = v[2]; q[3] = v[3];
-                    } else {
-#pragma unroll
-                        for (int c = 0; c < CH; ++c) q[c] = *(const uint32_t*)(packed + (e >> 1) + 4 * c);
-                    }
-                    const int64_t blk = e >> log2_bs;
-                    const float prod = code2_lds[q8[blk]] * scale2[blk >> 8];
-                    const float s = prod + offset;
-                    float part[B];
-#pragma unroll
-                    for (int b = 0; b < B; ++b) part[b] = 0.0f;
+        for (int r = 0; r < R; ++r) {
+            if (FULL || r < rows) {                                // wave-uniform
+                const uint8_t* codes = rb.codes[r] + (k0 >> 1);
+                if constexpr (CH == 4) {
+                    const u32x4 v = __builtin_nontemporal_load((const u32x4*)codes + lane);
+                    g.q[r][0] = v[0]; g.q[r][1] = v[1]; g.q[r][2] = v[2]; g.q[r][3] = v[3];
+                } else if constexpr (CH == 2) {
+                    const u32x2 v = __builtin_nontemporal_load((const u32x2*)codes + lane);
+                    g.q[r][0] = v[0]; g.q[r][1] = v[1];
+                } else {
 #pragma unroll
                     for (int c = 0; c < CH; ++c)
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const float hi = lut[(q[c] >> (8 * j + 4)) & 15u];
-                            const float lo = lut[(q[c] >> (8 * j)) & 15u];
-#pragma unroll
-                            for (int b = 0; b < B; ++b) {
-                                part[b] = __builtin_fmaf(hi, xf[b][8 * c + 2 * j], part[b]);
-                                part[b] = __builtin_fmaf(lo, xf[b][8 * c + 2 * j + 1], part[b]);
-                            }
-                        }
-#pragma unroll
-                    for (int b = 0; b < B; ++b) acc[r][b] = __builtin_fmaf(s, part[b], acc[r][b]);
+                        g.q[r][c] = __builtin_nontemporal_load((const uint32_t*)codes + lane * CH + c);
                 }
+                g.q8[r] = (rb.q8[r] + kb)[vb];
+                const int64_t gb = (int64_t)rb.blk_lo[r] + kb;     // block index relative to the row's group base
+                const uint32_t vg = ((uint32_t)(gb & 255) + vb) >> 8;
+                g.s2[r] = (rb.s2[r] + (gb >> 8))[vg];
+            } else {                                               // rows past N: level 0, scale code 0
+#pragma unroll
+                for (int c = 0; c < CH; ++c) g.q[r][c] = 0x77777777u;
+                g.q8[r] = 0;
+                g.s2[r] = 0.0f;
             }
         }
-    }
-
-    // wave64 butterfly, then the four waves' sums meet in LDS in wave order
-#pragma unroll
-    for (int r = 0; r < kRows; ++r)
 #pragma unroll
         for (int b = 0; b < B; ++b) {
-            float v = acc[r][b];
+            const half8_t* xb = (const half8_t*)(x + (int64_t)b * K + k0);
 #pragma unroll
-            for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
-            if (lane == 0) partial[wave][r][b] = v;
+            for (int c = 0; c < CH; ++c) g.xh[b][c] = xb[lane * CH + c];
         }
-    __syncthreads();
-    if (threadIdx.x < kRows * B) {
-        const int r = threadIdx.x / B, b = threadIdx.x % B;
-        if (r0 + r < N) {
-            float v = partial[0][r][b];
+    } else {                                                       // lanes past K in the last step
 #pragma unroll
-            for (int w = 1; w < kGWaves; ++w) v += partial[w][r][b];
-            y[(int64_t)b * N + r0 + r] = (_Float16)v;
+        for (int r = 0; r < R; ++r) {
+#pragma unroll
+            for (int c = 0; c < CH; ++c) g.q[r][c] = 0x77777777u;
+            g.q8[r] = 0;
+            g.s2[r] = 0.0f;
+        }
+#pragma unroll
+        for (int b = 0; b < B; ++b)
+#pragma unroll
+            for (int c = 0; c < CH; ++c) g.xh[b][c] = (half8_t)(_Float16)0;
+    }
+}
+
+// Eight level lookups for one dword of codes.  Two masked copies of the dword
+// hold code*4 (the LDS byte address) in each byte, so an address is one
+// bit-field extract; the empty asm keeps the compiler from undoing that.
+__device__ __forceinline__ void issue_lookups(uint32_t q, const float* lut, float (&lv)[8]) {
+    uint32_t lo4 = (q << 2) & 0x3C3C3C3Cu;                         // low nibbles  = odd elements
+    uint32_t hi4 = (q >> 2) & 0x3C3C3C3Cu;                         // high nibbles = even elements
+    asm("" : "+v"(lo4), "+v"(hi4));
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        lv[2 * j] = *(const float*)((const char*)lut + ((hi4 >> (8 * j)) & 0xFFu));
+        lv[2 * j + 1] = *(const float*)((const char*)lut + ((lo4 >> (8 * j)) & 0xFFu));
+    }
+}
+
+// Wait until at most `left` LDS operations of this wave are outstanding, and keep
+// the instruction scheduler from moving anything across.  The kernel is bound by
+// instruction issue, and a wave spends an issue slot on every s_waitcnt: one wait
+// per eight lookups instead of the one per multiply-add the compiler would emit.
+template <int LEFT>
+__device__ __forceinline__ void lds_wait() {
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_waitcnt(0xC07F | (LEFT << 8));              // lgkmcnt(LEFT); vmcnt, expcnt untouched
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+template <int B, int CH, int R>
+__device__ __forceinline__ void compute_step(const StepRegs<B, CH, R>& g, const float* lut, const float* code2_lds,
+                                             float offset, float (&acc)[R][B]) {
+    constexpr int U = R * CH;                                      // dwords of codes in this step
+    float c2[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) c2[r] = code2_lds[g.q8[r]];
+    float lv[2][8];
+    issue_lookups(g.q[0][0], lut, lv[0]);
+    float part[B];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {                                  // software pipeline, depth 2
+        const int r = u / CH, c = u % CH;
+        if (u + 1 < U) {
+            issue_lookups(g.q[(u + 1) / CH][(u + 1) % CH], lut, lv[(u + 1) & 1]);
+            lds_wait<8>();                                         // everything but the 8 just issued has landed
+        } else {
+            lds_wait<0>();
+        }
+        if (c == 0) {
+#pragma unroll
+            for (int b = 0; b < B; ++b) part[b] = 0.0f;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int b = 0; b < B; ++b) part[b] = __builtin_fmaf(lv[u & 1][j], (float)g.xh[b][c][j], part[b]);
+        if (c == CH - 1) {
+            const float prod = c2[r] * g.s2[r];                    // rounded product, then rounded sum
+            const float s = prod + offset;
+#pragma unroll
+            for (int b = 0; b < B; ++b) acc[r][b] = __builtin_fmaf(s, part[b], acc[r][b]);
         }
     }
 }
 
-template <int B, int CH>
+template <int B, int CH, int R, int OCC, bool FULL>
+__global__ __launch_bounds__(kWave, OCC) void gemv_kernel(const uint8_t* __restrict__ packed,
+                                                     const uint8_t* __restrict__ q8,
+                                                     const float* __restrict__ scale2,
+                                                     const float* __restrict__ offset_p,
+                                                     const float* __restrict__ code2, int log2_bs, int64_t N,
+                                                     int64_t K, const _Float16* __restrict__ x,
+                                                     _Float16* __restrict__ y) {
+    constexpr int E = 8 * CH;                 // elements per lane per step
+    constexpr int kSlice = E * kWave;         // elements per wave per step
+    __shared__ float lut[16];
+    __shared__ float code2_lds[256];
+
+    const int lane = threadIdx.x;
+    if (lane < 16) lut[lane] = __uint_as_float(gemv_level_literal(lane));
+#pragma unroll
+    for (int i = 0; i < 4; ++i) code2_lds[lane + 64 * i] = code2[lane + 64 * i];
+    gemv_lds_fence();
+    const float offset = offset_p[0];
+
+    const int64_t r0 = (int64_t)blockIdx.x * R;
+    const int rows = (N - r0) < R ? (int)(N - r0) : R;
+
+    float acc[R][B];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int b = 0; b < B; ++b) acc[r][b] = 0.0f;
+
+    // K % (8*CH) == 0, so a lane chunk is entirely inside or outside the row
+    const int64_t steps = (K + kSlice - 1) / kSlice;
+    // two register sets used alternately: the loads of one step are in flight
+    // while the other step is being consumed, and nothing is ever copied
+    RowBases<R> rb;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int64_t row_start = (r0 + (r < rows ? r : 0)) * K;   // rows past N alias row r0 and are never read
+        const int64_t row_blk = row_start >> log2_bs;
+        rb.codes[r] = packed + (row_start >> 1);
+        rb.q8[r] = q8 + row_blk;
+        rb.blk_lo[r] = (uint32_t)(row_blk & 255);
+        rb.s2[r] = scale2 + (row_blk >> 8);
+    }
+    StepRegs<B, CH, R> ping, pong;
+    load_step<B, CH, R, FULL>(ping, rb, x, log2_bs, K, rows, 0, lane);
+    for (int64_t it = 0;;) {
+        if (it + 1 < steps) load_step<B, CH, R, FULL>(pong, rb, x, log2_bs, K, rows, (it + 1) * kSlice, lane);
+        compute_step<B, CH, R>(ping, lut, code2_lds, offset, acc);
+        if (++it >= steps) break;
+        if (it + 1 < steps) load_step<B, CH, R, FULL>(ping, rb, x, log2_bs, K, rows, (it + 1) * kSlice, lane);
+        compute_step<B, CH, R>(pong, lut, code2_lds, offset, acc);
+        if (++it >= steps) break;
+    }
+
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int b = 0; b < B; ++b) {
+            const float total = wave_sum_to_lane63(acc[r][b]);
+            if (lane == kWave - 1 && r < rows) y[(int64_t)b * N + r0 + r] = (_Float16)total;
+        }
+}
+
+template <int B, int CH, int R, int OCC>
 static void launch_gemv(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
                         const float* code2, int log2_bs, int64_t N, int64_t K, const void* x, void* y,
                         hipStream_t s) {
-    const unsigned groups = (unsigned)((N + kRows - 1) / kRows);
-    hipLaunchKernelGGL((gemv_kernel<B, CH>), dim3(groups), dim3(kGThreads), 0, s, packed, q8, scale2, offset,
-                       code2, log2_bs, N, K, (const _Float16*)x, (_Float16*)y);
+    const unsigned groups = (unsigned)((N + R - 1) / R);
+    if (K % (8 * CH * kWave) == 0 && N % R == 0)
+        hipLaunchKernelGGL((gemv_kernel<B, CH, R, OCC, true>), dim3(groups), dim3(kWave), 0, s, packed, q8, scale2,
+                           offset, code2, log2_bs, N, K, (const _Float16*)x, (_Float16*)y);
+    else
+        hipLaunchKernelGGL((gemv_kernel<B, CH, R, OCC, false>), dim3(groups), dim3(kWave), 0, s, packed, q8, scale2,
+                           offset, code2, log2_bs, N, K, (const _Float16*)x, (_Float16*)y);
+}
+
+static int gemv_tokens(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
+                       const float* code2, int log2_bs, int64_t N, int64_t K, const _Float16* x, int B,
+                       _Float16* y, hipStream_t s) {
+#define NF4_GEMV_CASE(b, ch, r) \
+    case b: launch_gemv<b, ch, r, 2>(packed, q8, scale2, offset, code2, log2_bs, N, K, x, y, s); break;
+    switch (B) {
+        // (tokens, code dwords per lane per row, rows per wave): picked by sweeping on MI355X
+        NF4_GEMV_CASE(1, 4, 4) NF4_GEMV_CASE(2, 4, 4) NF4_GEMV_CASE(3, 2, 4) NF4_GEMV_CASE(4, 2, 4)
+        NF4_GEMV_CASE(5, 2, 4) NF4_GEMV_CASE(6, 2, 4) NF4_GEMV_CASE(7, 2, 4) NF4_GEMV_CASE(8, 2, 4)
+        default: return NF4_ERR_SHAPE;
+    }
+#undef NF4_GEMV_CASE
+    return record_hip(hipGetLastError());
 }
 
 }  // namespace nf4
@@ -148,7 +307,7 @@ extern "C" int nf4_dequant_gemv(const uint8_t* packed, const uint8_t* absmax_q8,
     if (log2_bs < 0) return NF4_ERR_BLOCKSIZE;
     if (B < 1 || B > 16) return NF4_ERR_SHAPE;
     if (N > 0 && (K <= 0 || K % blocksize != 0)) return NF4_ERR_SHAPE;   // blocksize is a multiple of 32
-    if (N > (int64_t)0x7fffffff / kRows * kRows) return NF4_ERR_SIZE;
+    if (N > 0x7fffffffLL) return NF4_ERR_SIZE;
     if (N == 0) return NF4_OK;
     if (!y) return NF4_ERR_NULL;
     if (!aligned(y, 2)) return NF4_ERR_ALIGN;
@@ -158,14 +317,14 @@ extern "C" int nf4_dequant_gemv(const uint8_t* packed, const uint8_t* absmax_q8,
         !aligned(code2, 4))
         return NF4_ERR_ALIGN;
 
-#define NF4_GEMV_CASE(b, ch) \
-    case b: launch_gemv<b, ch>(packed, absmax_q8, scale2, offset, code2, log2_bs, N, K, x, y, s); break;
-    switch (B) {
-        NF4_GEMV_CASE(1, 4) NF4_GEMV_CASE(2, 4) NF4_GEMV_CASE(3, 1) NF4_GEMV_CASE(4, 1)
-        NF4_GEMV_CASE(5, 1) NF4_GEMV_CASE(6, 1) NF4_GEMV_CASE(7, 1) NF4_GEMV_CASE(8, 1)
-        NF4_GEMV_CASE(9, 1) NF4_GEMV_CASE(10, 1) NF4_GEMV_CASE(11, 1) NF4_GEMV_CASE(12, 1)
-        NF4_GEMV_CASE(13, 1) NF4_GEMV_CASE(14, 1) NF4_GEMV_CASE(15, 1) NF4_GEMV_CASE(16, 1)
-    }
-#undef NF4_GEMV_CASE
-    return record_hip(hipGetLastError());
+    // More than 8 tokens go as two launches of at most 8 each: 16 tokens' worth of
+    // accumulators and activations do not fit the register file at a useful occupancy,
+    // and the path is ALU-bound there, so re-reading the codes costs little.
+    const int first = B > 8 ? (B + 1) / 2 : B;
+    int rc = gemv_tokens(packed, absmax_q8, scale2, offset, code2, log2_bs, N, K, (const _Float16*)x,
+                         first, (_Float16*)y, s);
+    if (rc == NF4_OK && B > first)
+        rc = gemv_tokens(packed, absmax_q8, scale2, offset, code2, log2_bs, N, K,
+                         (const _Float16*)x + (int64_t)first * K, B - first, (_Float16*)y + (int64_t)first * N, s);
+    return rc;
 }
