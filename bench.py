@@ -33,6 +33,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+FP32_FMA_PEAK_TFLOPS = 78.6                         # 256 CUs x 64 lanes x 2.4 GHz x 2, plain (unpacked) FP32 FMA
 BYTES_PER_ELEM = 0.5 + 4.0 / 64.0 + 2.0            # codes + fp32 absmax read, 16-bit value written
 BYTES_PER_ELEM_DQ = 0.5 + 1.0 / 64.0 + 4.0 / 16384.0 + 2.0
 GEMV_BYTES_PER_ELEM = 0.5 + 1.0 / 64.0 + 4.0 / 16384.0
@@ -260,9 +261,11 @@ def leg_gemv(torch, nf4, synth, stream, gen, src):
                                          N, K, x, B, y, stream=stream)
             us = time_on_stream(torch, stream, run, 5) / len(copies)
             gbps = n * GEMV_BYTES_PER_ELEM / (us * 1e-6) / 1e9
+            tflops = 2.0 * B * n / (us * 1e-6) / 1e12
             res[f"N{N}_K{K}_B{B}"] = {"us": round(us, 2), "GB/s": round(gbps, 1),
                                       "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
-                                      "TFLOP/s": round(2.0 * B * n / (us * 1e-6) / 1e12, 2)}
+                                      "TFLOP/s": round(tflops, 2), "bound": "alu",
+                                      "frac_of_fp32_fma_peak": round(tflops / FP32_FMA_PEAK_TFLOPS, 4)}
         del copies
     return res
 

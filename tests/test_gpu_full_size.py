@@ -1,0 +1,153 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch
+configuration bench.py times (same entry points, same argument shapes).
+
+The tensors are too large for an element-by-element oracle pass, so each test
+draws the weights on the GPU from a seeded generator, quantises them with
+nf4_quantize_ref, dequantises, and then (a) recomputes a random sample of
+quantisation blocks (plus the first and last ones) with the CPU oracle --
+both the quantiser's codes/scales and the dequantised values, bit for bit --
+and (b) checks a property that holds for every block of any tensor: a block's
+largest dequantised magnitude is its scale rounded to the output type (code 0
+or 15 is always present in a quantised block)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2604_02556_amd import binding as nf4
+from paper_2604_02556_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+SAMPLE = 4096
+
+
+def draw(n, sigma, seed, outlier_p=0.0):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    w = torch.empty(n, dtype=torch.float32, device="cuda").normal_(0.0, sigma, generator=g)
+    if outlier_p:
+        hit = torch.rand(n, device="cuda", generator=g) < outlier_p
+        w = torch.where(hit, w * 8.0, w)
+    return w
+
+
+def sample_blocks(nb, seed):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    idx = np.unique(np.concatenate([np.arange(8), np.arange(nb - 8, nb), rng.integers(0, nb, SAMPLE)]))
+    return idx
+
+
+def bits16(t):
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def check_sampled(w, bufs, out, idx, odt, absmax_host=None):
+    """Oracle on the sampled blocks: quantiser parity and dequantiser parity."""
+    ti = torch.from_numpy(idx).cuda()
+    src = w.view(-1, 64)[ti].cpu().numpy().reshape(-1)
+    pk = bufs["packed"].view(-1, 32)[ti].cpu().numpy().reshape(-1)
+    am = bufs["absmax"][ti].cpu().numpy()
+    got = bits16(out.view(torch.int16).view(-1, 64)[ti]).reshape(-1)
+    op, oa = oracle.quantize(src)
+    assert np.array_equal(oa, am), "quantize_ref absmax differs from the oracle on sampled blocks"
+    assert np.array_equal(op, pk), "quantize_ref codes differ from the oracle on sampled blocks"
+    scales = am if absmax_host is None else absmax_host[idx]
+    want = oracle.dequantize(pk, scales, src.size, out_dtype=odt)
+    bad = int((got != want).sum())
+    assert bad == 0, f"{bad} of {want.size} sampled elements differ"
+
+
+def check_block_extremes(out, scales_dev, tdt):
+    """max |out| over each block == |scale| rounded to the output type (any size)."""
+    peak = out.view(-1, 64).abs().amax(dim=1)
+    want = scales_dev.abs().to(tdt)
+    assert bool((peak == want).all().item())
+
+
+@pytest.mark.parametrize("name", list(synth.QWEN3_32B))
+def test_config1_qwen3_32b_shapes_fp16(name):
+    n = synth.numel(synth.QWEN3_32B[name])
+    w = draw(n, synth.QWEN3_32B_SIGMA, 1000 + len(name) + n % 17, outlier_p=0.001)
+    bufs = nf4.alloc_quantized(n)
+    nf4.nf4_quantize_ref(w, n, 64, bufs["packed"], bufs["absmax"])
+    out = torch.empty(n, dtype=torch.float16, device="cuda")
+    nf4.nf4_dequantize(bufs["packed"], bufs["absmax"], 64, n, out)
+    torch.cuda.synchronize()
+    check_sampled(w, bufs, out, sample_blocks(n // 64, n % 1009), oracle.FP16)
+    check_block_extremes(out, bufs["absmax"], torch.float16)
+
+
+@pytest.mark.parametrize("name", list(synth.GEMMA_27B))
+def test_config2_gemma_27b_shapes_double_quant_bf16(name):
+    n = synth.numel(synth.GEMMA_27B[name])
+    w = draw(n, synth.GEMMA_27B_SIGMA, 2000 + len(name) + n % 13)
+    bufs = nf4.alloc_quantized(n, dq=True)
+    nf4.nf4_quantize_ref(w, n, 64, bufs["packed"], bufs["absmax"], bufs["absmax_q8"], bufs["scale2"],
+                         bufs["offset"], bufs["code2"])
+    out = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    nf4.nf4_dequantize_dq(bufs["packed"], bufs["absmax_q8"], bufs["scale2"], bufs["offset"], bufs["code2"], 64,
+                          n, out)
+    torch.cuda.synchronize()
+    # second-level encoding: the whole arrays against the oracle (small: one byte per 64 elements)
+    absmax = bufs["absmax"].cpu().numpy()
+    q8, s2, off, c2 = oracle.dq_encode(absmax)
+    assert np.array_equal(bufs["absmax_q8"].cpu().numpy(), q8)
+    assert np.array_equal(bufs["scale2"].cpu().numpy(), s2)
+    assert bufs["offset"].cpu().numpy()[0] == off[0]
+    assert np.array_equal(bufs["code2"].cpu().numpy(), c2)
+    decoded = oracle.dq_decode(q8, s2, off, c2)
+    check_sampled(w, bufs, out, sample_blocks(n // 64, n % 1013), oracle.BF16, absmax_host=decoded)
+    check_block_extremes(out, torch.from_numpy(decoded).cuda(), torch.bfloat16)
+
+
+def test_config3_llama33_70b_layer_streamed_into_one_buffer():
+    """One decoder layer of the 70B-shaped stream, dequantised tensor after tensor into ONE reused FP16
+    buffer exactly as bench.py does; every tensor is checked before the next one overwrites it."""
+    shapes = synth.LLAMA33_70B
+    max_n = max(synth.numel(s) for s in shapes.values())
+    out = torch.empty(max_n, dtype=torch.float16, device="cuda")
+    stream = torch.cuda.Stream()
+    for ti, (name, shape) in enumerate(shapes.items()):
+        n = synth.numel(shape)
+        w = draw(n, synth.LLAMA33_70B_SIGMA, 3000 + ti)
+        bufs = nf4.alloc_quantized(n)
+        torch.cuda.synchronize()
+        nf4.nf4_quantize_ref(w, n, 64, bufs["packed"], bufs["absmax"], stream=stream)
+        nf4.nf4_dequantize(bufs["packed"], bufs["absmax"], 64, n, out, stream=stream)
+        stream.synchronize()
+        view = out[:n]
+        check_sampled(w, bufs, view, sample_blocks(n // 64, 3000 + ti), oracle.FP16)
+        check_block_extremes(view, bufs["absmax"], torch.float16)
+
+
+@pytest.mark.parametrize("N,K", synth.GEMV_SHAPES)
+def test_config4_gemv_70b_mlp_shapes(N, K):
+    n = N * K
+    w = draw(n, synth.LLAMA33_70B_SIGMA, 4000 + N % 7)
+    bufs = nf4.alloc_quantized(n, dq=True)
+    nf4.nf4_quantize_ref(w, n, 64, bufs["packed"], bufs["absmax"], bufs["absmax_q8"], bufs["scale2"],
+                         bufs["offset"], bufs["code2"])
+    torch.cuda.synchronize()
+    host = {k: v.cpu().numpy() for k, v in bufs.items()}
+    rng = np.random.Generator(np.random.PCG64(N + K))
+    rows = np.unique(np.concatenate([np.arange(5), np.arange(N - 5, N), rng.integers(0, N, 22)]))
+    for B in synth.GEMV_BATCHES:
+        x = synth.activations_fp16(B, K, seed=4100 + B)
+        y = torch.full((B, N), float("nan"), dtype=torch.float16, device="cuda")
+        nf4.nf4_dequant_gemv(bufs["packed"], bufs["absmax_q8"], bufs["scale2"], bufs["offset"], bufs["code2"], 64,
+                             N, K, torch.from_numpy(x).cuda(), B, y)
+        torch.cuda.synchronize()
+        yh = y.cpu().numpy().astype(np.float64)
+        assert np.isfinite(yh).all()
+        ref = np.empty((B, rows.size))
+        for j, r in enumerate(rows):
+            _, r64 = oracle.dequant_gemv_rows(host["packed"], host["absmax_q8"], host["scale2"], host["offset"],
+                                              host["code2"], N, K, x.view(np.uint16), int(r), 1)
+            ref[:, j] = r64[:, 0]
+        got = yh[:, rows]
+        rms = np.sqrt(np.mean(ref ** 2))
+        assert np.all(np.abs(got - ref) <= 1e-2 * np.abs(ref) + 1e-2 * rms)
+        rel = np.abs(got - ref).max() / np.abs(ref).max()
+        print(f"gemv N={N} K={K} B={B}: max err / max |y| = {rel:.2e}")
+        assert rel < 2e-3
