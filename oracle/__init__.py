@@ -23,7 +23,9 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        path = _build.build()
+        # NF4_ORACLE_LIB: load another build of the oracle instead.  Only the mutation
+        # tests set it, to show that a planted mistake makes the pins fail.
+        path = os.environ.get("NF4_ORACLE_LIB") or _build.build()
         L = ctypes.CDLL(path)
         c = ctypes
         vp, i64, i32 = c.c_void_p, c.c_int64, c.c_int
