@@ -107,6 +107,17 @@ int nf4_quantize_ref(const float* src, int64_t n, int blocksize, uint8_t* packed
                      uint8_t* absmax_q8, float* scale2, float* offset, float* code2,
                      void* stream);
 
+/*
+ * Tuned quantiser, first level only (Sec. II-B, forward direction): writes
+ * exactly the packed[] and absmax[] that nf4_quantize_ref writes, bit for bit,
+ * at HBM speed for blocksize 64 (other block sizes and the ragged end of a
+ * tensor run through the reference kernel).  src must be 16-byte aligned,
+ * packed 2-byte aligned.  The first call on a process builds a 512-byte table
+ * on the host (no device allocation).
+ */
+int nf4_quantize(const float* src, int64_t n, int blocksize, uint8_t* packed, float* absmax,
+                 void* stream);
+
 /* hipError_t (as int) behind the most recent NF4_ERR_HIP on the calling thread; 0 if none. */
 int nf4_last_hip_error(void);
 

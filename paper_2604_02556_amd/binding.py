@@ -39,7 +39,8 @@ def lib():
     L.nf4_dequantize_dq.argtypes = [vp, vp, vp, vp, vp, i32, i64, vp, i32, vp]
     L.nf4_dequant_gemv.argtypes = [vp, vp, vp, vp, vp, i32, i64, i64, vp, i32, vp, vp]
     L.nf4_quantize_ref.argtypes = [vp, i64, i32, vp, vp, vp, vp, vp, vp, vp]
-    for f in (L.nf4_dequantize, L.nf4_dequantize_dq, L.nf4_dequant_gemv, L.nf4_quantize_ref,
+    L.nf4_quantize.argtypes = [vp, i64, i32, vp, vp, vp]
+    for f in (L.nf4_dequantize, L.nf4_dequantize_dq, L.nf4_dequant_gemv, L.nf4_quantize_ref, L.nf4_quantize,
               L.nf4_last_hip_error):
         f.restype = i32
     L.nf4_last_hip_error.argtypes = []
@@ -101,6 +102,10 @@ def nf4_quantize_ref(src, n, blocksize, packed, absmax, absmax_q8=None, scale2=N
                      code2=None, stream=None):
     _check(lib().nf4_quantize_ref(_ptr(src), n, blocksize, _ptr(packed), _ptr(absmax), _ptr(absmax_q8),
                                   _ptr(scale2), _ptr(offset), _ptr(code2), _stream(stream)))
+
+
+def nf4_quantize(src, n, blocksize, packed, absmax, stream=None):
+    _check(lib().nf4_quantize(_ptr(src), n, blocksize, _ptr(packed), _ptr(absmax), _stream(stream)))
 
 
 # ---- allocation helpers (plumbing only: sizes of the format's arrays) ----

@@ -1,0 +1,217 @@
+// Tuned NF4 quantiser for gfx950 (blocksize 64): the forward direction of
+// Sec. II-B, bit-identical to the reference quantiser (and so to the CPU
+// definition), at HBM speed.
+//
+// Per block: absmax = max |x|; per element: x / absmax (IEEE division) mapped
+// to the nearest of the 16 levels, nearest meaning smallest |x/absmax - level|
+// evaluated in FP32, ties to the lower index.
+//
+// How the 16-way search is avoided without changing a single result.  For
+// adjacent levels k, k+1 the predicate "level k+1 is strictly nearer (in
+// rounded FP32 distance) than level k" is monotone in x, so it is equivalent to
+// x >= theta_k for one FP32 threshold theta_k, and the code of x is the number
+// of thresholds it reaches.  The 15 thresholds are found on the host at first
+// use by bisection over the FP32 number line with exactly that predicate
+// (plain FP32 subtract / abs / compare), not taken as midpoints: rounding moves
+// several of them by up to one ulp.  The thresholds are at least 0.08 apart, so
+// each of 64 bins of width 1/32 over [-1, 1] holds at most one; a bin stores
+// the count of thresholds below it and the one inside it (or +inf), and a code
+// costs one table read, one compare and one add.
+//
+// Data movement: one wave per 2048 elements; eight 128-bit loads per lane, each
+// contiguous across the wave; a quantisation block is then spread over the 16
+// lanes of one DPP row (4 elements each), so its absmax is 3 in-lane and 4 DPP
+// max operations and needs no LDS; codes leave as eight 2-byte stores per lane,
+// each instruction writing one full 128-byte line.
+#include <math.h>
+#include <string.h>
+
+#include <mutex>
+
+#include "nf4_device.hpp"
+#include "nf4_host.hpp"
+
+namespace nf4 {
+
+constexpr int kQTileElems = 2048;
+constexpr int kBins = 65;             // x / absmax = +1 lands in a bin of its own
+
+struct QuantBins {
+    float theta[kBins];      // the threshold inside the bin, +inf if none
+    uint32_t base[kBins];    // thresholds below the bin
+};
+
+// ---- host: thresholds and bins -------------------------------------------------
+
+static float host_level(int k) {
+    static const uint32_t bits[16] = {0xbf800000u, 0xbf3239b1u, 0xbf066b30u, 0xbeca32a0u, 0xbe91a24du, 0xbe3d353fu,
+                                      0xbdba7871u, 0x00000000u, 0x3da2faffu, 0x3e24cae3u, 0x3e7c04ddu, 0x3ead033au,
+                                      0x3ee1a4b8u, 0x3f1007abu, 0x3f3913b3u, 0x3f800000u};
+    float f;
+    memcpy(&f, &bits[k], 4);
+    return f;
+}
+
+// Monotone map between FP32 values and integers (for bisection over the number line).
+static int64_t float_key(float f) {
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    return (u >> 31) ? -(int64_t)(u & 0x7fffffffu) : (int64_t)u;
+}
+static float key_float(int64_t k) {
+    uint32_t u = k < 0 ? (0x80000000u | (uint32_t)(-k)) : (uint32_t)k;
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+static uint32_t bin_of(float xn) {                       // same arithmetic as the kernel; xn in [-1, 1]
+    const float pos = fmaf(xn, 32.0f, 32.0f);            // in [0, 64]
+    return pos <= 0.0f ? 0u : (uint32_t)pos;
+}
+
+static bool build_bins(QuantBins& qb) {
+    float theta[15];
+    for (int k = 0; k < 15; ++k) {
+        const float lo_level = host_level(k), hi_level = host_level(k + 1);
+        int64_t lo = float_key(lo_level), hi = float_key(hi_level);   // predicate false at lo, true at hi
+        while (hi - lo > 1) {
+            const int64_t mid = lo + (hi - lo) / 2;
+            const float x = key_float(mid);
+            const volatile float d_lo = fabsf(x - lo_level);
+            const volatile float d_hi = fabsf(x - hi_level);
+            if (d_hi < d_lo) hi = mid; else lo = mid;
+        }
+        theta[k] = key_float(hi);
+    }
+    for (int b = 0; b < kBins; ++b) { qb.theta[b] = INFINITY; qb.base[b] = 0; }
+    for (int k = 0; k < 15; ++k) {
+        const uint32_t b = bin_of(theta[k]);
+        if (qb.theta[b] != INFINITY) return false;       // two thresholds in one bin: never for NF4
+        qb.theta[b] = theta[k];
+        for (uint32_t later = b + 1; later < kBins; ++later) qb.base[later] += 1;
+    }
+    return true;
+}
+
+static const QuantBins* quant_bins() {
+    static QuantBins qb;
+    static bool ok = false;
+    static std::once_flag once;
+    std::call_once(once, [] { ok = build_bins(qb); });
+    return ok ? &qb : nullptr;
+}
+
+// ---- device --------------------------------------------------------------------
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_max(float v) {
+    // every lane has a valid source for these permutations; full masks + bound_ctrl let the
+    // compiler fold the move into the max (v_max_f32_dpp)
+    const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true);
+    return __builtin_fmaxf(v, __builtin_bit_cast(float, moved));
+}
+
+// x / a, correctly rounded, for a block scale a in [2^-64, 2^64] and |x| <= a.
+// `r` is the reciprocal of a refined once (shared by the block).  The sequence
+// is the textbook one -- quotient estimate, two residual corrections -- i.e.
+// the generic IEEE division without its range scaling, which is the identity
+// in this range.  Quotients so small that a residual underflows are far below
+// the smallest decision threshold (0.0398) and become code 7 either way.
+__device__ __forceinline__ float div_by_block_scale(float x, float a, float r) {
+    const float q0 = x * r;
+    const float e1 = __builtin_fmaf(-a, q0, x);
+    const float q1 = __builtin_fmaf(e1, r, q0);
+    const float e2 = __builtin_fmaf(-a, q1, x);
+    return __builtin_fmaf(e2, r, q1);
+}
+
+__global__ __launch_bounds__(kWave) void quantize_tiles_kernel(const float* __restrict__ src, QuantBins qb,
+                                                               uint8_t* __restrict__ packed,
+                                                               float* __restrict__ absmax) {
+    __shared__ float theta_lds[kBins];
+    __shared__ uint32_t base_lds[kBins];
+    const int lane = threadIdx.x;
+    theta_lds[lane] = qb.theta[lane];
+    base_lds[lane] = qb.base[lane];
+    if (lane == 0) {
+        theta_lds[kBins - 1] = qb.theta[kBins - 1];
+        base_lds[kBins - 1] = qb.base[kBins - 1];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+    const int64_t t = blockIdx.x;
+    const f32x4* in = (const f32x4*)(src + t * kQTileElems);
+    f32x4 v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = __builtin_nontemporal_load(in + j * kWave + lane);
+
+    uint16_t* out16 = (uint16_t*)(packed + t * (kQTileElems / 2));
+    float* amax_tile = absmax + t * (kQTileElems / 64);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        // lane holds elements 256 j + 4 lane .. + 3; block 4 j + lane / 16 is one DPP row
+        float a = __builtin_fmaxf(__builtin_fmaxf(fabsf(v[j][0]), fabsf(v[j][1])),
+                                  __builtin_fmaxf(fabsf(v[j][2]), fabsf(v[j][3])));
+        a = dpp_max<0xB1>(a);      // quad_perm [1,0,3,2]
+        a = dpp_max<0x4E>(a);      // quad_perm [2,3,0,1]
+        a = dpp_max<0x141>(a);     // row_half_mirror
+        a = dpp_max<0x140>(a);     // row_mirror: all 16 lanes hold the block's absmax
+        if ((lane & 15) == 0) amax_tile[4 * j + (lane >> 4)] = a;
+
+        float xn[4];
+        if (a >= 0x1p-64f && a <= 0x1p+64f) {             // same for the 16 lanes of the block
+            const float r0 = __builtin_amdgcn_rcpf(a);
+            const float r = __builtin_fmaf(__builtin_fmaf(-a, r0, 1.0f), r0, r0);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) xn[e] = div_by_block_scale(v[j][e], a, r);
+        } else {
+            const float div = a == 0.0f ? 1.0f : a;       // all-zero block: 0 / 1 = 0 -> code 7
+#pragma unroll
+            for (int e = 0; e < 4; ++e) xn[e] = v[j][e] / div;   // generic IEEE division
+        }
+        uint32_t code[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t b = (uint32_t)__builtin_fmaf(xn[e], 32.0f, 32.0f);   // 0..64; NaN -> 0
+            code[e] = base_lds[b] + (xn[e] >= theta_lds[b] ? 1u : 0u);
+        }
+        // element 2i in the high nibble of byte i; two bytes per lane, little-endian
+        const uint32_t two_bytes = (code[0] << 4) | code[1] | (code[2] << 12) | (code[3] << 8);
+        __builtin_nontemporal_store((uint16_t)two_bytes, out16 + j * 64 + lane);   // bytes 128 j + 2 lane
+    }
+}
+
+// the reference kernel (nf4_quantize_ref.hip) finishes what does not fill a tile
+int launch_quantize_ref_range(const float* src, int64_t n, int blocksize, uint8_t* packed, float* absmax,
+                              hipStream_t s);
+
+}  // namespace nf4
+
+extern "C" int nf4_quantize(const float* src, int64_t n, int blocksize, uint8_t* packed, float* absmax,
+                            void* stream) {
+    using namespace nf4;
+    if (n < 0) return NF4_ERR_SIZE;
+    if (log2_blocksize(blocksize) < 0) return NF4_ERR_BLOCKSIZE;
+    if (n == 0) return NF4_OK;
+    if (!src || !packed || !absmax) return NF4_ERR_NULL;
+    if (!aligned(src, 16) || !aligned(absmax, 4) || !aligned(packed, 2)) return NF4_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)stream;
+    const QuantBins* qb = quant_bins();
+    if (blocksize != 64 || qb == nullptr) return launch_quantize_ref_range(src, n, blocksize, packed, absmax, s);
+
+    const int64_t tiles = n / kQTileElems;
+    if (tiles > 0x7fffffffLL) return NF4_ERR_SIZE;
+    if (tiles > 0) {
+        hipLaunchKernelGGL(quantize_tiles_kernel, dim3((unsigned)tiles), dim3(kWave), 0, s, src, *qb, packed, absmax);
+        const int rc = record_hip(hipGetLastError());
+        if (rc != NF4_OK) return rc;
+    }
+    const int64_t done = tiles * kQTileElems;
+    if (done == n) return NF4_OK;
+    return launch_quantize_ref_range(src + done, n - done, 64, packed + done / 2, absmax + done / 64, s);
+}

@@ -115,6 +115,19 @@ __global__ __launch_bounds__(kQThreads) void dq_encode_kernel(const float* __res
     }
 }
 
+// First level only (codes and absmax) of a range that starts on a block boundary;
+// also used by the tuned quantiser for other block sizes and for ragged ends.
+int launch_quantize_ref_range(const float* src, int64_t n, int blocksize, uint8_t* packed, float* absmax,
+                              hipStream_t s) {
+    const int64_t nb = (n + blocksize - 1) / blocksize;
+    const int64_t cap = (int64_t)compute_units() * 16;
+    int64_t groups = (nb + kQWaves - 1) / kQWaves;
+    groups = groups < cap ? groups : cap;
+    hipLaunchKernelGGL(quantize_kernel, dim3((unsigned)groups), dim3(kQThreads), 0, s, src, n, blocksize, nb,
+                       packed, absmax);
+    return record_hip(hipGetLastError());
+}
+
 }  // namespace nf4
 
 extern "C" int nf4_quantize_ref(const float* src, int64_t n, int blocksize, uint8_t* packed, float* absmax,
@@ -133,11 +146,7 @@ extern "C" int nf4_quantize_ref(const float* src, int64_t n, int blocksize, uint
     hipStream_t s = (hipStream_t)stream;
     const int64_t nb = (n + blocksize - 1) / blocksize;
     const int64_t cap = (int64_t)compute_units() * 16;
-    int64_t groups = (nb + kQWaves - 1) / kQWaves;
-    groups = groups < cap ? groups : cap;
-    hipLaunchKernelGGL(quantize_kernel, dim3((unsigned)groups), dim3(kQThreads), 0, s, src, n, blocksize, nb,
-                       packed, absmax);
-    int rc = record_hip(hipGetLastError());
+    int rc = launch_quantize_ref_range(src, n, blocksize, packed, absmax, s);
     if (rc != NF4_OK || !dq) return rc;
 
     const int64_t ng = (nb + 255) / 256;

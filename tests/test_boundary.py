@@ -30,7 +30,7 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(L):
     names = declared_functions()
     assert set(names) >= {"nf4_dequantize", "nf4_dequantize_dq", "nf4_dequant_gemv", "nf4_quantize_ref",
-                          "nf4_last_hip_error", "nf4_status_string"}
+                          "nf4_quantize", "nf4_last_hip_error", "nf4_status_string"}
     for name in names:
         assert hasattr(L, name), name
 
@@ -98,6 +98,18 @@ def test_quantize_ref_argument_checks(L):
     assert f(P, 5, 64, P, None, None, None, None, None, None) == E_NULL
     assert f(P, 5, 64, P, P, P, None, P, P, None) == E_NULL             # DQ wants all four outputs
     assert f(P + 2, 5, 64, P, P, None, None, None, None, None) == E_ALIGN
+
+
+def test_quantize_argument_checks(L):
+    f = L.nf4_quantize
+    assert f(P, -1, 64, P, P, None) == E_SIZE
+    assert f(P, 5, 100, P, P, None) == E_BS
+    assert f(None, 0, 64, None, None, None) == OK
+    assert f(None, 5, 64, P, P, None) == E_NULL
+    assert f(P, 5, 64, None, P, None) == E_NULL
+    assert f(P, 5, 64, P, None, None) == E_NULL
+    assert f(P + 4, 5, 64, P, P, None) == E_ALIGN
+    assert f(P, 5, 64, P + 1, P, None) == E_ALIGN
 
 
 def test_binding_raises_with_the_status_name():
