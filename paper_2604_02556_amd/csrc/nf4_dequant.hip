@@ -51,26 +51,6 @@ struct ScaleArgs {
     const float* code2;
 };
 
-// Order LDS traffic within one wave: the hardware serves a wave's LDS
-// instructions in issue order, so only the compiler must be kept from moving
-// accesses across this point.
-__device__ __forceinline__ void wave_lds_fence() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-// level[i] as a bit pattern, selected from instruction literals.
-__device__ __forceinline__ uint32_t level_literal(uint32_t i) {
-    uint32_t v = 0xbf800000u;
-    v = i == 1 ? 0xbf3239b1u : v;  v = i == 2 ? 0xbf066b30u : v;  v = i == 3 ? 0xbeca32a0u : v;
-    v = i == 4 ? 0xbe91a24du : v;  v = i == 5 ? 0xbe3d353fu : v;  v = i == 6 ? 0xbdba7871u : v;
-    v = i == 7 ? 0x00000000u : v;  v = i == 8 ? 0x3da2faffu : v;  v = i == 9 ? 0x3e24cae3u : v;
-    v = i == 10 ? 0x3e7c04ddu : v; v = i == 11 ? 0x3ead033au : v; v = i == 12 ? 0x3ee1a4b8u : v;
-    v = i == 13 ? 0x3f1007abu : v; v = i == 14 ? 0x3f3913b3u : v; v = i == 15 ? 0x3f800000u : v;
-    return v;
-}
-
 // Eight codes of one dword -> eight scaled 16-bit values.  Byte j of the dword
 // holds element 2j in its high nibble and element 2j+1 in its low nibble.
 template <int DT>

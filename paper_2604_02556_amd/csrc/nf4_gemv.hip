@@ -30,22 +30,6 @@ namespace nf4 {
 
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 
-__device__ __forceinline__ uint32_t gemv_level_literal(uint32_t i) {
-    uint32_t v = 0xbf800000u;
-    v = i == 1 ? 0xbf3239b1u : v;  v = i == 2 ? 0xbf066b30u : v;  v = i == 3 ? 0xbeca32a0u : v;
-    v = i == 4 ? 0xbe91a24du : v;  v = i == 5 ? 0xbe3d353fu : v;  v = i == 6 ? 0xbdba7871u : v;
-    v = i == 7 ? 0x00000000u : v;  v = i == 8 ? 0x3da2faffu : v;  v = i == 9 ? 0x3e24cae3u : v;
-    v = i == 10 ? 0x3e7c04ddu : v; v = i == 11 ? 0x3ead033au : v; v = i == 12 ? 0x3ee1a4b8u : v;
-    v = i == 13 ? 0x3f1007abu : v; v = i == 14 ? 0x3f3913b3u : v; v = i == 15 ? 0x3f800000u : v;
-    return v;
-}
-
-__device__ __forceinline__ void gemv_lds_fence() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
 template <int CTRL, int ROW_MASK>
 __device__ __forceinline__ float dpp_add(float v) {
     const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xF, false);
@@ -219,10 +203,10 @@ __global__ __launch_bounds__(kWave, OCC) void gemv_kernel(const uint8_t* __restr
     __shared__ float code2_lds[256];
 
     const int lane = threadIdx.x;
-    if (lane < 16) lut[lane] = __uint_as_float(gemv_level_literal(lane));
+    if (lane < 16) lut[lane] = __uint_as_float(level_literal(lane));
 #pragma unroll
     for (int i = 0; i < 4; ++i) code2_lds[lane + 64 * i] = code2[lane + 64 * i];
-    gemv_lds_fence();
+    wave_lds_fence();
     const float offset = offset_p[0];
 
     const int64_t r0 = (int64_t)blockIdx.x * R;

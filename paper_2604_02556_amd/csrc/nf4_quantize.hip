@@ -44,11 +44,9 @@ struct QuantBins {
 // ---- host: thresholds and bins -------------------------------------------------
 
 static float host_level(int k) {
-    static const uint32_t bits[16] = {0xbf800000u, 0xbf3239b1u, 0xbf066b30u, 0xbeca32a0u, 0xbe91a24du, 0xbe3d353fu,
-                                      0xbdba7871u, 0x00000000u, 0x3da2faffu, 0x3e24cae3u, 0x3e7c04ddu, 0x3ead033au,
-                                      0x3ee1a4b8u, 0x3f1007abu, 0x3f3913b3u, 0x3f800000u};
+    const uint32_t bits = level_literal((uint32_t)k);
     float f;
-    memcpy(&f, &bits[k], 4);
+    memcpy(&f, &bits, 4);
     return f;
 }
 
@@ -140,9 +138,7 @@ __global__ __launch_bounds__(kWave) void quantize_tiles_kernel(const float* __re
         theta_lds[kBins - 1] = qb.theta[kBins - 1];
         base_lds[kBins - 1] = qb.base[kBins - 1];
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    wave_lds_fence();
 
     const int64_t t = blockIdx.x;
     const f32x4* in = (const f32x4*)(src + t * kQTileElems);
