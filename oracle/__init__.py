@@ -43,6 +43,8 @@ def lib():
         L.nf4o_dequant_gemv.argtypes = [vp, vp, vp, vp, vp, i32, i64, i64, vp, i32, vp, vp]
         L.nf4o_dequant_gemv_rows.argtypes = [vp, vp, vp, vp, vp, i32, i64, vp, i32, i64, i64, vp, vp]
         L.nf4o_dequant_gemv_rows.restype = None
+        L.nf4o_dequant_gemm_rows.argtypes = [vp, vp, vp, vp, vp, i32, i64, vp, i32, i64, i64, vp, vp]
+        L.nf4o_dequant_gemm_rows.restype = None
         for name in ("nf4o_table", "nf4o_dequantize", "nf4o_dequantize_range", "nf4o_dq_decode",
                      "nf4o_dequantize_dq", "nf4o_quantize", "nf4o_dq_encode", "nf4o_dequant_gemv"):
             getattr(L, name).restype = None
@@ -182,5 +184,25 @@ def dequant_gemv_rows(packed, q8, scale2, offset, code2, N, K, x_bits, r_first, 
     y = np.empty((B, r_count), dtype=np.uint16)
     y64 = np.empty((B, r_count), dtype=np.float64)
     lib().nf4o_dequant_gemv_rows(_p(packed), _p(q8), _p(scale2), _p(offset), _p(code2), blocksize, K,
+                                 _p(x_bits), B, r_first, r_count, _p(y), _p(y64))
+    return y, y64
+
+
+def dequant_gemm_rows(packed, q8, scale2, offset, code2, N, K, x_bits, r_first, r_count, blocksize=64):
+    """Like dequant_gemv_rows with every weight rounded to fp16 first (the dequantise-then-matmul flow)."""
+    x_bits = _chk(x_bits, np.uint16)
+    B = x_bits.size // K
+    n = N * K
+    nb = nblocks(n, blocksize)
+    packed = _chk(packed, np.uint8, (n + 1) // 2, "packed")
+    q8 = _chk(q8, np.uint8, nb, "absmax_q8")
+    scale2 = _chk(scale2, np.float32, (nb + 255) // 256, "scale2")
+    offset = _chk(offset, np.float32, 1, "offset")
+    code2 = _chk(code2, np.float32, 256, "code2")
+    if r_first < 0 or r_first + r_count > N:
+        raise ValueError("row range outside the matrix")
+    y = np.empty((B, r_count), dtype=np.uint16)
+    y64 = np.empty((B, r_count), dtype=np.float64)
+    lib().nf4o_dequant_gemm_rows(_p(packed), _p(q8), _p(scale2), _p(offset), _p(code2), blocksize, K,
                                  _p(x_bits), B, r_first, r_count, _p(y), _p(y64))
     return y, y64

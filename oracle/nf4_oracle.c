@@ -284,3 +284,29 @@ void nf4o_dequant_gemv(const uint8_t *packed, const uint8_t *absmax_q8, const fl
                        int64_t K, const uint16_t *x, int B, uint16_t *y, double *y_f64) {
     nf4o_dequant_gemv_rows(packed, absmax_q8, scale2, offset, code2, blocksize, K, x, B, 0, N, y, y_f64);
 }
+
+/* Fused dequantise + small-batch GEMM as the paper's flow defines it (Sec. III-A:
+ * the weights are dequantised to FP16 because the matrix units take 16-bit
+ * inputs, then multiplied with FP32 accumulation): the same sum as
+ * nf4o_dequant_gemv_rows, but every weight is first rounded to FP16,
+ * W16 = round_fp16(table[code] * scale).  Rows [r_first, r_first + r_count). */
+void nf4o_dequant_gemm_rows(const uint8_t *packed, const uint8_t *absmax_q8, const float *scale2,
+                            const float *offset, const float *code2, int blocksize, int64_t K,
+                            const uint16_t *x, int B, int64_t r_first, int64_t r_count,
+                            uint16_t *y, double *y_f64) {
+    for (int b = 0; b < B; ++b) {
+        for (int64_t r = r_first; r < r_first + r_count; ++r) {
+            double acc = 0.0;
+            for (int64_t k = 0; k < K; ++k) {
+                int64_t i = r * K + k;
+                float scale = dq_scale(absmax_q8, scale2, offset[0], code2, i / blocksize);
+                float w = NF4_LEVEL[code_of(packed, i)] * scale;
+                double w16 = f16_bits_to_double(nf4o_f32_to_f16(w));
+                acc += f16_bits_to_double(x[(int64_t)b * K + k]) * w16;
+            }
+            int64_t o = (int64_t)b * r_count + (r - r_first);
+            if (y_f64) y_f64[o] = acc;
+            if (y) y[o] = nf4o_f32_to_f16((float)acc);
+        }
+    }
+}

@@ -32,6 +32,7 @@ MUTATIONS = [
     ("second-level code truncated instead of rounded", "float r = rintf(scaled / s);", "float r = truncf(scaled / s);"),
     ("second-level offset is the median-free zero", "float off = nb > 0 ? (float)(sum / (double)nb) : 0.0f;", "float off = 0.0f;"),
     ("gemv reads activations backwards", "f16_bits_to_double(x[(int64_t)b * K + k])", "f16_bits_to_double(x[(int64_t)b * K + (K - 1 - k)])"),
+    ("gemm weight not rounded to fp16", "double w16 = f16_bits_to_double(nf4o_f32_to_f16(w));", "double w16 = (double)w;"),
     ("gemv weight rounded to fp16 first", "acc += f16_bits_to_double(x[(int64_t)b * K + k]) * (double)w;",
      "acc += f16_bits_to_double(x[(int64_t)b * K + k]) * f16_bits_to_double(nf4o_f32_to_f16(w));"),
 ]

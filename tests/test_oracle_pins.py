@@ -372,3 +372,23 @@ def test_zero_level_times_negative_scale_is_negative_zero():
     assert np.all(out == 0x8000)
     outb = oracle.dequantize(packed, np.array([-2.0], np.float32), 64, out_dtype=oracle.BF16)
     assert np.all(outb == 0x8000)
+
+
+def test_gemm_equals_float64_matmul_of_fp16_dequantized_weights():
+    # the dequantise-to-FP16-then-matmul flow, rewritten with library routines
+    N, K, B = 24, 256, 5
+    p, q8, s2, off, c2, x = _small_gemv_case(N, K, B, seed=51)
+    w16 = f16(oracle.dequantize_dq(p, q8, s2, off, c2, N * K, out_dtype=oracle.FP16)).reshape(N, K)
+    _, y64 = oracle.dequant_gemm_rows(p, q8, s2, off, c2, N, K, x.view(np.uint16), 0, N)
+    want = x.astype(np.float64) @ w16.astype(np.float64).T
+    assert np.allclose(y64, want, rtol=1e-12, atol=1e-12)
+    _, part = oracle.dequant_gemm_rows(p, q8, s2, off, c2, N, K, x.view(np.uint16), 3, 4)
+    assert np.array_equal(part, y64[:, 3:7])
+    # unit vector -> the FP16 dequantised column, exactly
+    e = np.zeros((1, K), np.float16)
+    e[0, 77] = 1
+    _, col = oracle.dequant_gemm_rows(p, q8, s2, off, c2, N, K, e.view(np.uint16), 0, N)
+    assert np.array_equal(col[0], w16[:, 77].astype(np.float64))
+    # and it differs from the unrounded GEMV where rounding the weights matters
+    _, y_exact = oracle.dequant_gemv(p, q8, s2, off, c2, N, K, x.view(np.uint16))
+    assert not np.array_equal(y_exact, y64) and np.allclose(y_exact, y64, rtol=0, atol=2e-3 * np.abs(y64).max())
