@@ -233,6 +233,9 @@ def leg_dq(torch, nf4, synth, stream, gen, src):
             "note": "0.98 GB per pass: partly served by the 256 MB last-level cache"}
 
 
+GEMM_BATCHES = (1, 4, 16, 32, 64)
+
+
 def leg_gemv(torch, nf4, synth, stream, gen, src):
     """y = x W^T on the 70B MLP shapes, double-quantised W, batch 1/4/16; 4 distinct W copies are cycled
     so that the 112 MiB of codes come from HBM rather than the last-level cache."""
@@ -267,6 +270,21 @@ def leg_gemv(torch, nf4, synth, stream, gen, src):
                                       "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
                                       "TFLOP/s": round(tflops, 2), "bound": "alu",
                                       "frac_of_fp32_fma_peak": round(tflops / FP32_FMA_PEAK_TFLOPS, 4)}
+        # the matrix-core variant (weights rounded to FP16 in registers), the paper's batch range
+        for B in GEMM_BATCHES:
+            gen.manual_seed(6100 + B)
+            x = torch.empty((B, K), dtype=torch.float32, device=dev).normal_(generator=gen).to(torch.float16)
+            y = torch.empty((B, N), dtype=torch.float16, device=dev)
+
+            def run_mm():
+                for b in copies:
+                    nf4.nf4_dequant_gemm(b["packed"], b["absmax_q8"], b["scale2"], b["offset"], b["code2"], 64,
+                                         N, K, x, B, y, stream=stream)
+            us = time_on_stream(torch, stream, run_mm, 5) / len(copies)
+            gbps = n * GEMV_BYTES_PER_ELEM / (us * 1e-6) / 1e9
+            res[f"mfma_N{N}_K{K}_B{B}"] = {"us": round(us, 2), "GB/s": round(gbps, 1),
+                                           "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
+                                           "TFLOP/s": round(2.0 * B * n / (us * 1e-6) / 1e12, 2)}
         del copies
     return res
 

@@ -93,6 +93,20 @@ int nf4_dequant_gemv(const uint8_t* packed, const uint8_t* absmax_q8, const floa
                      int64_t K, const void* x, int B, void* y, void* stream);
 
 /*
+ * Fused dequantise + small-batch GEMM on the matrix cores, for the paper's batch
+ * range (Sec. VI-A: 2 to 64).  It is the paper's quantised matmul (Sec. III-A,
+ * III-C: dequantise W to FP16, then an FP16 matmul with FP32 accumulation)
+ * without the FP16 copy of W in memory:
+ *   y[b][r] = rne_fp16( sum_k x[b][k] * W16[r][k] ),
+ *   W16[r][k] = rne_fp16( level[code(r*K + k)] * scale((r*K + k) / blocksize) ).
+ * Same arguments and layouts as nf4_dequant_gemv; 1 <= B <= 64, K > 0 and
+ * K % blocksize == 0 (else NF4_ERR_SHAPE).  packed and x 16-byte aligned.
+ */
+int nf4_dequant_gemm(const uint8_t* packed, const uint8_t* absmax_q8, const float* scale2,
+                     const float* offset, const float* code2, int blocksize, int64_t N,
+                     int64_t K, const void* x, int B, void* y, void* stream);
+
+/*
  * Reference-quality (untuned) quantiser, the forward direction of Sec. II-B:
  * per block absmax = max |src|, code = nearest level to src / absmax (FP32
  * distance, ties to the lower index, all-zero block -> absmax 0 and code 7,

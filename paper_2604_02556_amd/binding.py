@@ -38,6 +38,8 @@ def lib():
     L.nf4_dequantize.argtypes = [vp, vp, i32, i64, vp, i32, vp]
     L.nf4_dequantize_dq.argtypes = [vp, vp, vp, vp, vp, i32, i64, vp, i32, vp]
     L.nf4_dequant_gemv.argtypes = [vp, vp, vp, vp, vp, i32, i64, i64, vp, i32, vp, vp]
+    L.nf4_dequant_gemm.argtypes = [vp, vp, vp, vp, vp, i32, i64, i64, vp, i32, vp, vp]
+    L.nf4_dequant_gemm.restype = i32
     L.nf4_quantize_ref.argtypes = [vp, i64, i32, vp, vp, vp, vp, vp, vp, vp]
     L.nf4_quantize.argtypes = [vp, i64, i32, vp, vp, vp]
     for f in (L.nf4_dequantize, L.nf4_dequantize_dq, L.nf4_dequant_gemv, L.nf4_quantize_ref, L.nf4_quantize,
@@ -94,6 +96,12 @@ def nf4_dequantize_dq(packed, absmax_q8, scale2, offset, code2, blocksize, n, ou
 
 def nf4_dequant_gemv(packed, absmax_q8, scale2, offset, code2, blocksize, N, K, x, B, y, stream=None):
     _check(lib().nf4_dequant_gemv(_ptr(packed), _ptr(absmax_q8), _ptr(scale2), _ptr(offset), _ptr(code2),
+                                  blocksize, N, K, _ptr(x), B, _ptr(y), _stream(stream)))
+    return y
+
+
+def nf4_dequant_gemm(packed, absmax_q8, scale2, offset, code2, blocksize, N, K, x, B, y, stream=None):
+    _check(lib().nf4_dequant_gemm(_ptr(packed), _ptr(absmax_q8), _ptr(scale2), _ptr(offset), _ptr(code2),
                                   blocksize, N, K, _ptr(x), B, _ptr(y), _stream(stream)))
     return y
 

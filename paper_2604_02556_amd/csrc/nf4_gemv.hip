@@ -128,31 +128,6 @@ __device__ __forceinline__ void load_step(StepRegs<B, CH, R>& g, const RowBases<
     }
 }
 
-// Eight level lookups for one dword of codes.  Two masked copies of the dword
-// hold code*4 (the LDS byte address) in each byte, so an address is one
-// bit-field extract; the empty asm keeps the compiler from undoing that.
-__device__ __forceinline__ void issue_lookups(uint32_t q, const float* lut, float (&lv)[8]) {
-    uint32_t lo4 = (q << 2) & 0x3C3C3C3Cu;                         // low nibbles  = odd elements
-    uint32_t hi4 = (q >> 2) & 0x3C3C3C3Cu;                         // high nibbles = even elements
-    asm("" : "+v"(lo4), "+v"(hi4));
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        lv[2 * j] = *(const float*)((const char*)lut + ((hi4 >> (8 * j)) & 0xFFu));
-        lv[2 * j + 1] = *(const float*)((const char*)lut + ((lo4 >> (8 * j)) & 0xFFu));
-    }
-}
-
-// Wait until at most `left` LDS operations of this wave are outstanding, and keep
-// the instruction scheduler from moving anything across.  The kernel is bound by
-// instruction issue, and a wave spends an issue slot on every s_waitcnt: one wait
-// per eight lookups instead of the one per multiply-add the compiler would emit.
-template <int LEFT>
-__device__ __forceinline__ void lds_wait() {
-    __builtin_amdgcn_sched_barrier(0);
-    __builtin_amdgcn_s_waitcnt(0xC07F | (LEFT << 8));              // lgkmcnt(LEFT); vmcnt, expcnt untouched
-    __builtin_amdgcn_sched_barrier(0);
-}
-
 template <int B, int CH, int R>
 __device__ __forceinline__ void compute_step(const StepRegs<B, CH, R>& g, const float* lut, const float* code2_lds,
                                              float offset, float (&acc)[R][B]) {

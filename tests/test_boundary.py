@@ -30,7 +30,7 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(L):
     names = declared_functions()
     assert set(names) >= {"nf4_dequantize", "nf4_dequantize_dq", "nf4_dequant_gemv", "nf4_quantize_ref",
-                          "nf4_quantize", "nf4_last_hip_error", "nf4_status_string"}
+                          "nf4_quantize", "nf4_dequant_gemm", "nf4_last_hip_error", "nf4_status_string"}
     for name in names:
         assert hasattr(L, name), name
 
@@ -87,6 +87,20 @@ def test_gemv_argument_checks(L):
     assert f(*a, 64, 4, 64, P, 1, None, None) == E_NULL
     assert f(*a, 64, 4, 64, P + 2, 1, P, None) == E_ALIGN
     assert f(*a, 64, 4, 64, P, 1, P + 1, None) == E_ALIGN
+
+
+def test_gemm_argument_checks(L):
+    f = L.nf4_dequant_gemm
+    a = [P] * 5
+    assert f(*a, 64, -1, 64, P, 1, P, None) == E_SIZE
+    assert f(*a, 48, 4, 64, P, 1, P, None) == E_BS
+    assert f(*a, 64, 4, 64, P, 0, P, None) == E_SHAPE
+    assert f(*a, 64, 4, 64, P, 65, P, None) == E_SHAPE
+    assert f(*a, 64, 4, 96, P, 1, P, None) == E_SHAPE
+    assert f(*a, 64, 0, 64, P, 1, P, None) == OK
+    assert f(*a, 64, 4, 64, None, 1, P, None) == E_NULL
+    assert f(*a, 64, 4, 64, P, 1, None, None) == E_NULL
+    assert f(*a, 64, 4, 64, P + 2, 1, P, None) == E_ALIGN
 
 
 def test_quantize_ref_argument_checks(L):

@@ -151,3 +151,35 @@ def test_config4_gemv_70b_mlp_shapes(N, K):
         rel = np.abs(got - ref).max() / np.abs(ref).max()
         print(f"gemv N={N} K={K} B={B}: max err / max |y| = {rel:.2e}")
         assert rel < 2e-3
+
+
+@pytest.mark.parametrize("N,K", synth.GEMV_SHAPES)
+def test_gemm_70b_mlp_shapes_batches_16_and_64(N, K):
+    n = N * K
+    w = draw(n, synth.LLAMA33_70B_SIGMA, 5000 + N % 7)
+    bufs = nf4.alloc_quantized(n, dq=True)
+    nf4.nf4_quantize_ref(w, n, 64, bufs["packed"], bufs["absmax"], bufs["absmax_q8"], bufs["scale2"],
+                         bufs["offset"], bufs["code2"])
+    torch.cuda.synchronize()
+    host = {k: v.cpu().numpy() for k, v in bufs.items()}
+    rng = np.random.Generator(np.random.PCG64(N + K + 1))
+    rows = np.unique(np.concatenate([np.arange(3), np.arange(N - 3, N), rng.integers(0, N, 10)]))
+    for B in (16, 64):
+        x = synth.activations_fp16(B, K, seed=5100 + B)
+        y = torch.full((B, N), float("nan"), dtype=torch.float16, device="cuda")
+        nf4.nf4_dequant_gemm(bufs["packed"], bufs["absmax_q8"], bufs["scale2"], bufs["offset"], bufs["code2"], 64,
+                             N, K, torch.from_numpy(x).cuda(), B, y)
+        torch.cuda.synchronize()
+        yh = y.cpu().numpy().astype(np.float64)
+        assert np.isfinite(yh).all()
+        ref = np.empty((B, rows.size))
+        for j, r in enumerate(rows):
+            _, r64 = oracle.dequant_gemm_rows(host["packed"], host["absmax_q8"], host["scale2"], host["offset"],
+                                              host["code2"], N, K, x.view(np.uint16), int(r), 1)
+            ref[:, j] = r64[:, 0]
+        got = yh[:, rows]
+        rms = np.sqrt(np.mean(ref ** 2))
+        assert np.all(np.abs(got - ref) <= 1e-2 * np.abs(ref) + 1e-2 * rms)
+        rel = np.abs(got - ref).max() / np.abs(ref).max()
+        print(f"gemm N={N} K={K} B={B}: max err / max |y| = {rel:.2e}")
+        assert rel < 2e-3
