@@ -1,0 +1,61 @@
+"""The library only enqueues kernels on the caller's stream (no allocation, no
+synchronisation, no memset), so its calls can be captured in a HIP graph.  The
+graph is replayed several times with eager work and synchronisation between
+the replays, and every replay must reproduce the eager results bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2604_02556_amd import binding as nf4
+from paper_2604_02556_amd import synth
+from gpu_util import dev
+
+pytestmark = pytest.mark.gpu
+
+
+def test_captured_calls_replay_bit_exactly():
+    n = 64 * 4096 + 1000
+    N, K, B = 96, 1024, 20
+    w = synth.gaussian_weights(n, 0.02, 1)
+    p, a = oracle.quantize(w)
+    q8, s2, off, c2 = oracle.dq_encode(a)
+    wm = synth.gaussian_weights(N * K, 0.015, 2)
+    pm, am = oracle.quantize(wm)
+    mq8, ms2, moff, mc2 = oracle.dq_encode(am)
+    x = synth.activations_fp16(B, K, 3)
+
+    d = {k: dev(v) for k, v in dict(p=p, a=a, q8=q8, s2=s2, off=off, c2=c2, pm=pm, mq8=mq8, ms2=ms2, moff=moff,
+                                    mc2=mc2, x=x, w=w).items()}
+    out16 = torch.empty(n, dtype=torch.float16, device="cuda")
+    outbf = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    yv = torch.empty((8, N), dtype=torch.float16, device="cuda")
+    ym = torch.empty((B, N), dtype=torch.float16, device="cuda")
+    qp = torch.empty((n + 1) // 2, dtype=torch.uint8, device="cuda")
+    qa = torch.empty((n + 63) // 64, dtype=torch.float32, device="cuda")
+    outputs = [out16, outbf, yv, ym, qp, qa]
+
+    def run(stream):
+        nf4.nf4_dequantize(d["p"], d["a"], 64, n, out16, stream=stream)
+        nf4.nf4_dequantize_dq(d["p"], d["q8"], d["s2"], d["off"], d["c2"], 64, n, outbf, stream=stream)
+        nf4.nf4_dequant_gemv(d["pm"], d["mq8"], d["ms2"], d["moff"], d["mc2"], 64, N, K, d["x"], 8, yv, stream=stream)
+        nf4.nf4_dequant_gemm(d["pm"], d["mq8"], d["ms2"], d["moff"], d["mc2"], 64, N, K, d["x"], B, ym, stream=stream)
+        nf4.nf4_quantize(d["w"], n, 64, qp, qa, stream=stream)
+
+    side = torch.cuda.Stream()
+    run(side)                                              # eager reference (also warms up lazy initialisation)
+    side.synchronize()
+    want = [t.clone() for t in outputs]
+    assert np.array_equal(want[0].view(torch.int16).cpu().numpy().view(np.uint16), oracle.dequantize(p, a, n))
+
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        run(torch.cuda.current_stream())
+    for replay in range(4):
+        for t in outputs:                                  # eager work between replays: poison the outputs
+            t.view(torch.uint8).fill_(0xA5)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip(outputs, want):
+            assert torch.equal(got.view(torch.uint8), ref.view(torch.uint8)), f"replay {replay} differs"
