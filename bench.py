@@ -48,6 +48,8 @@ def parse():
     ap.add_argument("--layers", type=int, default=None, help="override the 80 layers (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true")
+    ap.add_argument("--extra-legs", default="dq,gemv,quantize,layer",
+                    help="comma list of the extra legs to run: dq, gemv, quantize, layer")
     ap.add_argument("--per-shape", action="store_true", help="also time each tensor shape on its own")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="finish with one plain 256 MiB -> 256 MiB device copy (calibrates rocprofv3 byte counters)")
@@ -168,10 +170,13 @@ def main():
     if args.per_shape:
         result["per_shape"] = per_shape(torch, nf4, stream, tensors, names, out)
     if not args.no_extra:
-        result["extra"] = {"dq_bf16_gemma27b": leg_dq(torch, nf4, synth, stream, gen, src),
-                           "gemv_70b_mlp": leg_gemv(torch, nf4, synth, stream, gen, src),
-                           "quantize_70b_gate": leg_quantize(torch, nf4, synth, stream, gen, src),
-                           "layer_replay_qwen3_32b": leg_layer_replay(torch, nf4, synth, stream, gen, src)}
+        legs = {"dq": ("dq_bf16_gemma27b", leg_dq), "gemv": ("gemv_70b_mlp", leg_gemv),
+                "quantize": ("quantize_70b_gate", leg_quantize), "layer": ("layer_replay_qwen3_32b", leg_layer_replay)}
+        result["extra"] = {}
+        for key in args.extra_legs.split(","):
+            if key:
+                name, fn = legs[key.strip()]
+                result["extra"][name] = fn(torch, nf4, synth, stream, gen, src)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(tensors[:len(names)])
     print(json.dumps(result))
