@@ -1,0 +1,81 @@
+"""GPU parity, randomised: many small tensors with random element counts, block
+sizes, output types and scale kinds, each compared bit for bit with the oracle.
+Seeded, so the set of cases is the same on every run."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2604_02556_amd import binding as nf4
+from paper_2604_02556_amd import synth
+from gpu_util import dev, guard_intact, mismatches, out_buffer, bits
+
+pytestmark = pytest.mark.gpu
+
+
+def test_random_dequantize_cases():
+    rng = np.random.Generator(np.random.PCG64(2024))
+    for case in range(150):
+        bs = int(rng.choice([64, 64, 64, 128, 256, 512, 1024, 2048, 4096]))
+        n = int(rng.integers(1, 3 * 2048 + 4096 + 100)) if case % 3 else int(rng.integers(1, 200))
+        bf16 = bool(rng.integers(0, 2))
+        dq = bool(rng.integers(0, 2))
+        tdt, odt = (torch.bfloat16, oracle.BF16) if bf16 else (torch.float16, oracle.FP16)
+        packed = synth.random_codes((n + 1) // 2, seed=10_000 + case)
+        nb = oracle.nblocks(n, bs)
+        whole, out = out_buffer(n, tdt)
+        if dq:
+            q8 = rng.integers(0, 256, nb, dtype=np.uint8)
+            s2 = rng.uniform(-2, 2, (nb + 255) // 256).astype(np.float32)
+            off = rng.uniform(-0.5, 0.5, 1).astype(np.float32)
+            c2 = np.sort(rng.uniform(-1, 1, 256)).astype(np.float32)
+            want = oracle.dequantize_dq(packed, q8, s2, off, c2, n, blocksize=bs, out_dtype=odt)
+            nf4.nf4_dequantize_dq(dev(packed), dev(q8), dev(s2), dev(off), dev(c2), bs, n, out)
+        else:
+            absmax = synth.positive_scales(nb, seed=20_000 + case, lo=1e-7, hi=1e5)
+            want = oracle.dequantize(packed, absmax, n, blocksize=bs, out_dtype=odt)
+            nf4.nf4_dequantize(dev(packed), dev(absmax), bs, n, out)
+        torch.cuda.synchronize()
+        bad = mismatches(bits(out), want, bf16)
+        assert bad == 0, f"case {case}: n={n} bs={bs} bf16={bf16} dq={dq}: {bad} mismatches"
+        assert guard_intact(whole, n), f"case {case}: wrote past the end"
+
+
+def test_random_quantize_cases():
+    rng = np.random.Generator(np.random.PCG64(2025))
+    for case in range(60):
+        bs = int(rng.choice([64, 64, 64, 128, 512, 4096]))
+        n = int(rng.integers(1, 5 * 2048 + 300))
+        w = synth.gaussian_weights(n, float(rng.uniform(1e-4, 3.0)), seed=30_000 + case, outlier_p=0.01)
+        if case % 4 == 0:
+            w[rng.integers(0, n, max(1, n // 7))] = 0.0
+        p, a = oracle.quantize(w, bs)
+        for fn in (nf4.nf4_quantize, nf4.nf4_quantize_ref):
+            bufs = nf4.alloc_quantized(n, bs)
+            bufs["packed"].fill_(0xCD)
+            fn(dev(w), n, bs, bufs["packed"], bufs["absmax"])
+            torch.cuda.synchronize()
+            assert np.array_equal(bufs["absmax"].cpu().numpy()[:a.size], a), f"case {case} n={n} bs={bs} {fn.__name__}"
+            assert np.array_equal(bufs["packed"].cpu().numpy()[:p.size], p), f"case {case} n={n} bs={bs} {fn.__name__}"
+
+
+def test_random_gemv_and_gemm_cases():
+    rng = np.random.Generator(np.random.PCG64(2026))
+    for case in range(40):
+        bs = int(rng.choice([64, 64, 128, 256]))
+        K = bs * int(rng.integers(1, 20))
+        N = int(rng.integers(1, 90))
+        w = synth.gaussian_weights(N * K, 0.015, seed=40_000 + case)
+        p, a = oracle.quantize(w, bs)
+        q8, s2, off, c2 = oracle.dq_encode(a)
+        for B, fn, ofn in ((int(rng.integers(1, 17)), nf4.nf4_dequant_gemv, oracle.dequant_gemv_rows),
+                           (int(rng.integers(1, 65)), nf4.nf4_dequant_gemm, oracle.dequant_gemm_rows)):
+            x = synth.activations_fp16(B, K, seed=50_000 + case)
+            _, ref = ofn(p, q8, s2, off, c2, N, K, x.view(np.uint16), 0, N, blocksize=bs)
+            y = torch.full((B, N), float("nan"), dtype=torch.float16, device="cuda")
+            fn(dev(p), dev(q8), dev(s2), dev(off), dev(c2), bs, N, K, dev(x), B, y)
+            torch.cuda.synchronize()
+            yh = y.cpu().numpy().astype(np.float64)
+            rms = np.sqrt(np.mean(ref ** 2)) + 1e-30
+            ok = np.abs(yh - ref) <= 1e-2 * np.abs(ref) + 1e-2 * rms
+            assert ok.all(), f"case {case}: N={N} K={K} bs={bs} B={B} {fn.__name__}"
