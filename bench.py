@@ -50,7 +50,6 @@ def parse():
     ap.add_argument("--no-extra", action="store_true")
     ap.add_argument("--extra-legs", default="dq,gemv,quantize,layer",
                     help="comma list of the extra legs to run: dq, gemv, quantize, layer")
-    ap.add_argument("--per-shape", action="store_true", help="also time each tensor shape on its own")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="finish with one plain 256 MiB -> 256 MiB device copy (calibrates rocprofv3 byte counters)")
     return ap.parse_args()
@@ -167,8 +166,9 @@ def main():
         torch.cuda.synchronize()
         b.copy_(a)                                      # reads 268435456 bytes, writes 268435456 bytes
         torch.cuda.synchronize()
-    if args.per_shape:
-        result["per_shape"] = per_shape(torch, nf4, stream, tensors, names, out)
+    result["per_shape"] = per_shape(torch, nf4, stream, tensors, names, out)
+    result["sum_of_kernel_times_ms_per_step"] = round(sum(v["us"] for v in result["per_shape"].values())
+                                                      * layers / 1e3, 4)
     if not args.no_extra:
         legs = {"dq": ("dq_bf16_gemma27b", leg_dq), "gemv": ("gemv_70b_mlp", leg_gemv),
                 "quantize": ("quantize_70b_gate", leg_quantize), "layer": ("layer_replay_qwen3_32b", leg_layer_replay)}
@@ -393,9 +393,18 @@ def cpu_baseline(layer_tensors):
             for j in jobs:
                 j.result()
     dt = time.perf_counter() - t0
+    # one thread on a 1024 x 1024 tensor (the small parity configuration), for scale
+    n0 = 1024 * 1024
+    p0, a0 = host[0][1][:n0 // 2], host[0][2][:n0 // 64]
+    t1 = time.perf_counter()
+    for _ in range(5):
+        oracle.dequantize(p0, a0, n0)
+    dt1 = (time.perf_counter() - t1) / 5
     return {"value": round(elems * BYTES_PER_ELEM / dt / 1e9, 3), "unit": "GB/s", "cores": threads,
             "kind": "oracle", "elements_per_s": round(elems / dt, 1), "seconds": round(dt, 2),
-            "sample": f"layer 0 of the stream (7 tensors, {elems} elements), fp16 output"}
+            "sample": f"layer 0 of the stream (7 tensors, {elems} elements), fp16 output",
+            "single_thread_1024x1024": {"GB/s": round(n0 * BYTES_PER_ELEM / dt1 / 1e9, 3),
+                                        "elements_per_s": round(n0 / dt1, 1), "ms": round(dt1 * 1e3, 2)}}
 
 
 if __name__ == "__main__":
