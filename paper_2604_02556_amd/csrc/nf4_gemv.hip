@@ -11,7 +11,7 @@
 //     summation order is fixed (deterministic results);
 //   * per step lane l owns CH consecutive dwords of codes of each row (8*CH
 //     elements, always inside one quantisation block): one 128-bit (CH=4) or
-//     32-bit (CH=1) load per row, contiguous across the wave.  The loads of
+//     64-bit (CH=2) load per row, contiguous across the wave.  The loads of
 //     step i+1 are issued before the arithmetic of step i;
 //   * its 8*CH activations per token stay FP16 in registers and enter the FP32
 //     multiply-add directly (mixed-precision FMA), reused for all R rows;
@@ -164,8 +164,8 @@ __device__ __forceinline__ void compute_step(const StepRegs<B, CH, R>& g, const 
     }
 }
 
-template <int B, int CH, int R, int OCC, bool FULL>
-__global__ __launch_bounds__(kWave, OCC) void gemv_kernel(const uint8_t* __restrict__ packed,
+template <int B, int CH, int R, bool FULL>
+__global__ __launch_bounds__(kWave, 2) void gemv_kernel(const uint8_t* __restrict__ packed,
                                                      const uint8_t* __restrict__ q8,
                                                      const float* __restrict__ scale2,
                                                      const float* __restrict__ offset_p,
@@ -227,16 +227,16 @@ __global__ __launch_bounds__(kWave, OCC) void gemv_kernel(const uint8_t* __restr
         }
 }
 
-template <int B, int CH, int R, int OCC>
+template <int B, int CH, int R>
 static void launch_gemv(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
                         const float* code2, int log2_bs, int64_t N, int64_t K, const void* x, void* y,
                         hipStream_t s) {
     const unsigned groups = (unsigned)((N + R - 1) / R);
     if (K % (8 * CH * kWave) == 0 && N % R == 0)
-        hipLaunchKernelGGL((gemv_kernel<B, CH, R, OCC, true>), dim3(groups), dim3(kWave), 0, s, packed, q8, scale2,
+        hipLaunchKernelGGL((gemv_kernel<B, CH, R, true>), dim3(groups), dim3(kWave), 0, s, packed, q8, scale2,
                            offset, code2, log2_bs, N, K, (const _Float16*)x, (_Float16*)y);
     else
-        hipLaunchKernelGGL((gemv_kernel<B, CH, R, OCC, false>), dim3(groups), dim3(kWave), 0, s, packed, q8, scale2,
+        hipLaunchKernelGGL((gemv_kernel<B, CH, R, false>), dim3(groups), dim3(kWave), 0, s, packed, q8, scale2,
                            offset, code2, log2_bs, N, K, (const _Float16*)x, (_Float16*)y);
 }
 
@@ -244,7 +244,7 @@ static int gemv_tokens(const uint8_t* packed, const uint8_t* q8, const float* sc
                        const float* code2, int log2_bs, int64_t N, int64_t K, const _Float16* x, int B,
                        _Float16* y, hipStream_t s) {
 #define NF4_GEMV_CASE(b, ch, r) \
-    case b: launch_gemv<b, ch, r, 2>(packed, q8, scale2, offset, code2, log2_bs, N, K, x, y, s); break;
+    case b: launch_gemv<b, ch, r>(packed, q8, scale2, offset, code2, log2_bs, N, K, x, y, s); break;
     switch (B) {
         // (tokens, code dwords per lane per row, rows per wave): picked by sweeping on MI355X
         NF4_GEMV_CASE(1, 4, 4) NF4_GEMV_CASE(2, 4, 4) NF4_GEMV_CASE(3, 2, 4) NF4_GEMV_CASE(4, 2, 4)
