@@ -291,6 +291,20 @@ def leg_gemv(torch, nf4, synth, stream, gen, src):
             res[f"mfma_N{N}_K{K}_B{B}"] = {"us": round(us, 2), "GB/s": round(gbps, 1),
                                            "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
                                            "TFLOP/s": round(2.0 * B * n / (us * 1e-6) / 1e12, 2)}
+            # the same with K split across workgroups (caller-provided workspace); both kernels of a call timed
+            ws = torch.empty(nf4.nf4_dequant_gemm_workspace_bytes(N, K, B), dtype=torch.uint8, device=dev)
+
+            def run_sk():
+                for b in copies:
+                    nf4.nf4_dequant_gemm(b["packed"], b["absmax_q8"], b["scale2"], b["offset"], b["code2"], 64,
+                                         N, K, x, B, y, workspace=ws, stream=stream)
+            us = time_on_stream(torch, stream, run_sk, 5) / len(copies)
+            gbps = n * GEMV_BYTES_PER_ELEM / (us * 1e-6) / 1e9
+            res[f"mfma_splitk_N{N}_K{K}_B{B}"] = {"us": round(us, 2), "GB/s": round(gbps, 1),
+                                                  "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
+                                                  "TFLOP/s": round(2.0 * B * n / (us * 1e-6) / 1e12, 2),
+                                                  "workspace_bytes": ws.numel()}
+            del ws
         del copies
     return res
 
@@ -360,15 +374,26 @@ def leg_layer_replay(torch, nf4, synth, stream, gen, src):
                 nf4.nf4_dequant_gemm(b["packed"], b["absmax_q8"], b["scale2"], b["offset"], b["code2"], 64, N, K,
                                      xs[K], B, ys[N], stream=stream)
 
+        ws = torch.empty(max(nf4.nf4_dequant_gemm_workspace_bytes(N, K, B) for _, N, K, _ in tensors),
+                         dtype=torch.uint8, device=dev)
+
+        def fused_splitk():
+            for _, N, K, b in tensors:
+                nf4.nf4_dequant_gemm(b["packed"], b["absmax_q8"], b["scale2"], b["offset"], b["code2"], 64, N, K,
+                                     xs[K], B, ys[N], workspace=ws, stream=stream)
+
         t_deq = time_on_stream(torch, stream, deq_all, 10)
         t_mm = time_on_stream(torch, stream, mm_all, 10)
         t_both = time_on_stream(torch, stream, both, 10)
         t_fused = time_on_stream(torch, stream, fused, 10)
+        t_sk = time_on_stream(torch, stream, fused_splitk, 10)
         res[f"B{B}"] = {"dequant_us": round(t_deq, 1), "fp16_matmul_us": round(t_mm, 1),
                         "dequant_then_matmul_us": round(t_both, 1),
                         "dequant_share_of_quantized_matmul": round(t_deq / (t_deq + t_mm), 3),
                         "fused_dequant_gemm_us": round(t_fused, 1),
-                        "fused_speedup": round(t_both / t_fused, 2)}
+                        "fused_speedup": round(t_both / t_fused, 2),
+                        "fused_splitk_us": round(t_sk, 1),
+                        "fused_splitk_speedup": round(t_both / t_sk, 2)}
     res["note"] = ("7 projections of one layer, double-quantised NF4, one pass; the paper's A100 baseline spends "
                    "72.4 % of quantised-matmul time in dequantisation at batch 8 (Sec. III-C)")
     return res

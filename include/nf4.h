@@ -40,6 +40,7 @@
 #ifndef NF4_H
 #define NF4_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -101,10 +102,27 @@ int nf4_dequant_gemv(const uint8_t* packed, const uint8_t* absmax_q8, const floa
  *   W16[r][k] = rne_fp16( level[code(r*K + k)] * scale((r*K + k) / blocksize) ).
  * Same arguments and layouts as nf4_dequant_gemv; 1 <= B <= 64, K > 0 and
  * K % blocksize == 0 (else NF4_ERR_SHAPE).  packed and x 16-byte aligned.
+ *
+ * workspace (device, 16-byte aligned, owned by the caller, contents undefined
+ * before and after) selects the algorithm:
+ *   NULL     : one kernel; every workgroup sums over all of K and re-reads x
+ *              from L2 (workspace_bytes is ignored);
+ *   non-NULL : K is split across workgroups that share x through LDS; FP32
+ *              partial sums go to the workspace and a second kernel adds them in
+ *              a fixed order.  Faster from about 16 tokens on.  workspace_bytes
+ *              must be at least nf4_dequant_gemm_workspace_bytes(N, K, B), else
+ *              NF4_ERR_SIZE.  Calls that share a workspace must not overlap.
+ * Both give the sum above with FP32 accumulation; the order of the additions
+ * differs, each is deterministic.
  */
 int nf4_dequant_gemm(const uint8_t* packed, const uint8_t* absmax_q8, const float* scale2,
                      const float* offset, const float* code2, int blocksize, int64_t N,
-                     int64_t K, const void* x, int B, void* y, void* stream);
+                     int64_t K, const void* x, int B, void* y, void* workspace,
+                     size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace the split-K path of nf4_dequant_gemm needs for this shape
+ * on the current device (0 for shapes nf4_dequant_gemm rejects). */
+size_t nf4_dequant_gemm_workspace_bytes(int64_t N, int64_t K, int B);
 
 /*
  * Reference-quality (untuned) quantiser, the forward direction of Sec. II-B:

@@ -38,8 +38,10 @@ def lib():
     L.nf4_dequantize.argtypes = [vp, vp, i32, i64, vp, i32, vp]
     L.nf4_dequantize_dq.argtypes = [vp, vp, vp, vp, vp, i32, i64, vp, i32, vp]
     L.nf4_dequant_gemv.argtypes = [vp, vp, vp, vp, vp, i32, i64, i64, vp, i32, vp, vp]
-    L.nf4_dequant_gemm.argtypes = [vp, vp, vp, vp, vp, i32, i64, i64, vp, i32, vp, vp]
+    L.nf4_dequant_gemm.argtypes = [vp, vp, vp, vp, vp, i32, i64, i64, vp, i32, vp, vp, c.c_size_t, vp]
     L.nf4_dequant_gemm.restype = i32
+    L.nf4_dequant_gemm_workspace_bytes.argtypes = [i64, i64, i32]
+    L.nf4_dequant_gemm_workspace_bytes.restype = c.c_size_t
     L.nf4_quantize_ref.argtypes = [vp, i64, i32, vp, vp, vp, vp, vp, vp, vp]
     L.nf4_quantize.argtypes = [vp, i64, i32, vp, vp, vp]
     for f in (L.nf4_dequantize, L.nf4_dequantize_dq, L.nf4_dequant_gemv, L.nf4_quantize_ref, L.nf4_quantize,
@@ -100,10 +102,18 @@ def nf4_dequant_gemv(packed, absmax_q8, scale2, offset, code2, blocksize, N, K, 
     return y
 
 
-def nf4_dequant_gemm(packed, absmax_q8, scale2, offset, code2, blocksize, N, K, x, B, y, stream=None):
+def nf4_dequant_gemm(packed, absmax_q8, scale2, offset, code2, blocksize, N, K, x, B, y, workspace=None,
+                     stream=None):
+    """workspace: a device tensor of at least nf4_dequant_gemm_workspace_bytes(N, K, B) bytes, or None."""
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib().nf4_dequant_gemm(_ptr(packed), _ptr(absmax_q8), _ptr(scale2), _ptr(offset), _ptr(code2),
-                                  blocksize, N, K, _ptr(x), B, _ptr(y), _stream(stream)))
+                                  blocksize, N, K, _ptr(x), B, _ptr(y), _ptr(workspace), ws_bytes,
+                                  _stream(stream)))
     return y
+
+
+def nf4_dequant_gemm_workspace_bytes(N, K, B):
+    return int(lib().nf4_dequant_gemm_workspace_bytes(N, K, B))
 
 
 def nf4_quantize_ref(src, n, blocksize, packed, absmax, absmax_q8=None, scale2=None, offset=None,

@@ -64,6 +64,23 @@ __device__ __forceinline__ uint32_t pack2<NF4_BF16>(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, h);
 }
 
+// rne_fp16(rne_fp32(a * s)) for two values, packed (`lo` product in the low half).
+// Written as a fused multiply-add with a -0 addend: a * s + (-0) is the rounded
+// FP32 product with its sign of zero kept, and the compiler turns the FP32 FMA
+// followed by the narrowing into one mixed-precision instruction per value
+// (v_fma_mixlo_f16 / v_fma_mixhi_f16) instead of multiply, multiply, convert.
+// `neg_zero` must come from opaque_neg_zero(): a visible constant would let the
+// compiler fold the FMA back into a multiply.
+__device__ __forceinline__ float opaque_neg_zero() {
+    float z = -0.0f;
+    asm("" : "+s"(z));
+    return z;
+}
+__device__ __forceinline__ uint32_t scaled_pack2_f16(float lo, float hi, float s, float neg_zero) {
+    half2_t h = {(_Float16)__builtin_fmaf(lo, s, neg_zero), (_Float16)__builtin_fmaf(hi, s, neg_zero)};
+    return __builtin_bit_cast(uint32_t, h);
+}
+
 // One value.  The empty asm pins `v` as a finished FP32 result: without it the
 // compiler folds a preceding multiply into a mixed-precision multiply-add with
 // a +0 addend, which turns a product of -0 into +0.

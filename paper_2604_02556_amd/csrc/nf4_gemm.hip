@@ -65,6 +65,7 @@ __global__ __launch_bounds__(kMWaves * kWave) void gemm_kernel(const uint8_t* __
     for (int i = tid; i < 256; i += kMThreads) code2_lds[i] = code2[i];
     __syncthreads();
     const float offset = offset_p[0];
+    const float nz = opaque_neg_zero();
 
     const int lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -142,7 +143,7 @@ __global__ __launch_bounds__(kMWaves * kWave) void gemm_kernel(const uint8_t* __
                 const float sj = s[j >> 1];
                 u32x4 a;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) a[i] = pack2<NF4_FP16>(lv[j & 1][2 * i] * sj, lv[j & 1][2 * i + 1] * sj);
+                for (int i = 0; i < 4; ++i) a[i] = scaled_pack2_f16(lv[j & 1][2 * i], lv[j & 1][2 * i + 1], sj, nz);
                 const half8_t ah = __builtin_bit_cast(half8_t, a);
 #pragma unroll
                 for (int t = 0; t < TG; ++t)
@@ -183,9 +184,17 @@ static void launch_gemm(const uint8_t* packed, const uint8_t* q8, const float* s
 
 }  // namespace nf4
 
+extern "C" size_t nf4_dequant_gemm_workspace_bytes(int64_t N, int64_t K, int B) {
+    if (N <= 0 || K <= 0 || B < 1 || B > 64) return 0;
+    const nf4::SplitPlan p = nf4::plan_split(N, K, B);
+    // at least one byte, so that a caller who passes a workspace always gets the split-K path
+    return p.splits > 1 ? (size_t)p.splits * (size_t)B * (size_t)N * sizeof(float) : 16;
+}
+
 extern "C" int nf4_dequant_gemm(const uint8_t* packed, const uint8_t* absmax_q8, const float* scale2,
                                 const float* offset, const float* code2, int blocksize, int64_t N,
-                                int64_t K, const void* x, int B, void* y, void* stream) {
+                                int64_t K, const void* x, int B, void* y, void* workspace,
+                                size_t workspace_bytes, void* stream) {
     using namespace nf4;
     if (N < 0 || K < 0) return NF4_ERR_SIZE;
     const int log2_bs = log2_blocksize(blocksize);
@@ -201,6 +210,12 @@ extern "C" int nf4_dequant_gemm(const uint8_t* packed, const uint8_t* absmax_q8,
     hipStream_t s = (hipStream_t)stream;
     const _Float16* xp = (const _Float16*)x;
     _Float16* yp = (_Float16*)y;
+    if (workspace) {
+        if (!aligned(workspace, 16)) return NF4_ERR_ALIGN;
+        if (workspace_bytes < nf4_dequant_gemm_workspace_bytes(N, K, B)) return NF4_ERR_SIZE;
+        return launch_gemm_splitk(packed, absmax_q8, scale2, offset, code2, log2_bs, N, K, xp, B, yp,
+                                  (float*)workspace, s);
+    }
     // (token groups, row groups per wave, waves per workgroup = split of K), picked by sweeping on MI355X:
     // sharing the activation registers between row groups halves the L2 traffic that bounds this kernel,
     // but matrices with few rows need the smaller tile to fill the machine.

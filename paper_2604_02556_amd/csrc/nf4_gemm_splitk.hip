@@ -1,0 +1,279 @@
+// Fused NF4 dequantise + small-batch GEMM, split along K across workgroups, with
+// the activations staged through LDS (same arithmetic as nf4_gemm.hip: the
+// paper's quantised matmul of Sec. III-A / III-C with the FP16 copy of W kept in
+// registers; y[b][r] = sum_k x[b][k] * rne_fp16(level[code] * scale)).
+//
+// The single-launch kernel lets every wave fetch its own activation operands
+// from L2, and that traffic -- every workgroup re-reads all of x -- bounds it.
+// Here the W waves of a workgroup work on the SAME window of 256 k for W
+// different groups of 16 RG rows, so one copy of the window's activations
+// (16 TG tokens x 512 bytes) in LDS serves them all: the workgroup loads it once,
+// coalesced, one window ahead, into the other half of a double buffer, and the
+// waves read their MFMA B operands from it with ds_read_b128.  Token rows are
+// 528 bytes apart, so the 16 lanes that the LDS serves together fall into 8
+// distinct groups of 4 banks (conflict-free at the rate of a 128-bit read).  The
+// codes of the next window are requested into registers while the current one
+// is expanded.  (Requesting two windows ahead, spreading the loads over the
+// arithmetic steps and unpredicated fast paths were each measured and changed
+// nothing: with one barrier per window the 16 waves move in lockstep through a
+// phase that queues in the address unit, one that queues in the LDS and one that
+// is bound by instruction issue, and the window lasts the sum of the three.)
+//
+// Since all waves of a workgroup share k, K is split across workgroups instead:
+// blockIdx.y = split s takes `wps` consecutive windows and writes its partial
+// 16 x 16 tiles to partial[s][token][row] (FP32) in the caller's workspace; a
+// second kernel adds the S partials in order of s (deterministic) and rounds to
+// FP16.  With S = 1 the first kernel writes y itself.
+#include "nf4_device.hpp"
+#include "nf4_host.hpp"
+
+namespace nf4 {
+
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kSkWindow = 256;               // k per step
+constexpr int kSkRowStride = 36;             // dwords per row in the code exchange buffer (32 + padding)
+constexpr int kXRowBytes = 528;              // bytes per token row of the activation tile (512 + 16)
+
+template <int TG, int RG, int W>
+__global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* __restrict__ packed,
+                                                                const uint8_t* __restrict__ q8,
+                                                                const float* __restrict__ scale2,
+                                                                const float* __restrict__ offset_p,
+                                                                const float* __restrict__ code2, int log2_bs,
+                                                                int64_t N, int64_t K,
+                                                                const _Float16* __restrict__ x, int B, int wps,
+                                                                float* __restrict__ partial,
+                                                                _Float16* __restrict__ y) {
+    constexpr int kThreads = W * kWave;
+    constexpr int kTokens = 16 * TG;
+    constexpr int kChunks = kTokens * 32;        // 16-byte pieces of one activation tile
+    constexpr int kU = (kChunks + kThreads - 1) / kThreads;
+    __shared__ float lut[16];
+    __shared__ float code2_lds[256];
+    __shared__ __attribute__((aligned(16))) uint32_t stage[W][RG][16 * kSkRowStride];
+    __shared__ __attribute__((aligned(16))) uint8_t xtile[2][kTokens * kXRowBytes];
+
+    const int tid = threadIdx.x;
+    if (tid < 16) lut[tid] = __uint_as_float(level_literal(tid));
+    for (int i = tid; i < 256; i += kThreads) code2_lds[i] = code2[i];
+    const float offset = offset_p[0];
+    const float nz = opaque_neg_zero();
+
+    const int lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int sub = lane & 15;                   // row of a tile (A) / token of a group (B, C)
+    const int g = lane >> 4;                     // lane group
+    const int64_t row0 = ((int64_t)blockIdx.x * W + wave) * (16 * RG);
+    const int64_t k_begin = (int64_t)blockIdx.y * wps * kSkWindow;
+    const int64_t k_stop = k_begin + (int64_t)wps * kSkWindow;
+    const int64_t k_end = k_stop < K ? k_stop : K;       // multiple of 64
+
+    // ---- loaders.  K and k_end are multiples of 64, so each 8-, 32- or 64-wide piece is all in or all out.
+    u32x4 c[RG][2];                              // codes: 16-byte groups g and g + 4 of the row's 128 bytes
+    uint32_t qb[RG];                             // 8-bit scale code and second-level scale of the window's
+    float s2[RG];                                //   g-th 64-element quarter
+    u32x4 xr[kU];                                // this thread's pieces of the activation tile
+    auto load_codes = [&](int64_t kw) {
+#pragma unroll
+        for (int r = 0; r < RG; ++r) {
+            const int64_t row = row0 + 16 * r + sub;
+            const bool row_ok = row < N;
+            const int64_t e0 = row * K + kw;     // flat index of the row's first element in the window
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                c[r][h] = (u32x4){0x77777777u, 0x77777777u, 0x77777777u, 0x77777777u};   // level 0 if not loaded
+                if (row_ok && kw + 32 * (g + 4 * h) < k_end)
+                    c[r][h] = __builtin_nontemporal_load((const u32x4*)(packed + (e0 >> 1)) + g + 4 * h);
+            }
+            qb[r] = 0;
+            s2[r] = 0.0f;
+            if (row_ok && kw + 64 * g < k_end) {
+                const int64_t blk = (e0 + 64 * g) >> log2_bs;
+                qb[r] = q8[blk];
+                s2[r] = scale2[blk >> 8];
+            }
+        }
+    };
+    auto load_x = [&](int64_t kw) {
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const int piece = tid + u * kThreads;
+            const int token = piece >> 5, kc = piece & 31;
+            xr[u] = (u32x4){0u, 0u, 0u, 0u};
+            if (piece < kChunks && token < B && kw + 8 * kc < k_end)
+                xr[u] = *(const u32x4*)(x + (int64_t)token * K + kw + 8 * kc);
+        }
+    };
+    auto store_x = [&](int buf) {
+#pragma unroll
+        for (int u = 0; u < kU; ++u) {
+            const int piece = tid + u * kThreads;
+            const int token = piece >> 5, kc = piece & 31;
+            if (piece < kChunks) *(u32x4*)(&xtile[buf][token * kXRowBytes + kc * 16]) = xr[u];
+        }
+    };
+
+    f32x4 acc[RG][TG];
+#pragma unroll
+    for (int r = 0; r < RG; ++r)
+#pragma unroll
+        for (int t = 0; t < TG; ++t) acc[r][t] = (f32x4){0.0f, 0.0f, 0.0f, 0.0f};
+
+    load_codes(k_begin);
+    load_x(k_begin);
+    store_x(0);
+    __syncthreads();                             // lut, code2_lds and the first tile are in place
+
+    int buf = 0;
+    for (int64_t kw = k_begin; kw < k_end; kw += kSkWindow, buf ^= 1) {
+        // ---- scale of the window's g-th quarter: rounded product, then rounded sum
+        float mine[RG];
+#pragma unroll
+        for (int r = 0; r < RG; ++r) {
+            const float prod = code2_lds[qb[r]] * s2[r];
+            mine[r] = (row0 + 16 * r + sub < N && kw + 64 * g < k_end) ? prod + offset : 0.0f;
+        }
+        // ---- codes cross lanes: group j of the row goes to dwords 4 j .. 4 j + 3; lane group g reads dword g
+#pragma unroll
+        for (int r = 0; r < RG; ++r) {
+            uint32_t* my_row = &stage[wave][r][sub * kSkRowStride];
+            *(u32x4*)(my_row + 4 * g) = c[r][0];
+            *(u32x4*)(my_row + 4 * (g + 4)) = c[r][1];
+        }
+        wave_lds_fence();
+        uint32_t q[RG][8];
+#pragma unroll
+        for (int r = 0; r < RG; ++r)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) q[r][j] = stage[wave][r][sub * kSkRowStride + 4 * j + g];
+        float s[RG][4];                          // quarter jj of the window: k = 64 jj .. -> MFMA steps 2 jj, 2 jj + 1
+#pragma unroll
+        for (int r = 0; r < RG; ++r)
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj)
+                s[r][jj] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((sub + 16 * jj) << 2,
+                                                                                  __builtin_bit_cast(int, mine[r])));
+        wave_lds_fence();                        // q is in registers: the exchange buffer may be reused
+
+        // ---- the next window's codes and activations start their way from memory now
+        load_codes(kw + kSkWindow);
+        load_x(kw + kSkWindow);
+
+        // ---- dequantise to FP16 in registers and multiply: lookups pipelined two dwords deep
+        const uint8_t* xt = &xtile[buf][sub * kXRowBytes + 16 * g];
+        float lv[2][8];
+        issue_lookups(q[0][0], lut, lv[0]);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            half8_t xb[TG];
+#pragma unroll
+            for (int t = 0; t < TG; ++t) xb[t] = *(const half8_t*)(xt + t * 16 * kXRowBytes + 64 * j);
+#pragma unroll
+            for (int r = 0; r < RG; ++r) {
+                const int p = j * RG + r;
+                if (p + 1 < 8 * RG) {
+                    issue_lookups(q[(p + 1) % RG][(p + 1) / RG], lut, lv[(p + 1) & 1]);
+                    lds_wait<8>();
+                } else {
+                    lds_wait<0>();
+                }
+                const float sj = s[r][j >> 1];
+                u32x4 a;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) a[i] = scaled_pack2_f16(lv[p & 1][2 * i], lv[p & 1][2 * i + 1], sj, nz);
+                const half8_t ah = __builtin_bit_cast(half8_t, a);
+#pragma unroll
+                for (int t = 0; t < TG; ++t)
+                    acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah, xb[t], acc[r][t], 0, 0, 0);
+            }
+        }
+
+        store_x(buf ^ 1);                        // nobody reads that half before the barrier
+        __syncthreads();                         // ... and nobody is still reading it: all passed the previous one
+    }
+
+    // ---- C tile: lane holds token 16 t + sub, rows 4 g .. 4 g + 3 of the row group
+#pragma unroll
+    for (int r = 0; r < RG; ++r)
+#pragma unroll
+        for (int t = 0; t < TG; ++t) {
+            const int token = 16 * t + sub;
+            const int64_t rr = row0 + 16 * r + 4 * g;
+            if (token >= B || rr >= N) continue;
+            if (partial) {
+                float* p = partial + ((int64_t)blockIdx.y * B + token) * N + rr;
+                if ((N & 3) == 0) {
+                    *(f32x4*)p = acc[r][t];
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (rr + i < N) p[i] = acc[r][t][i];
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (rr + i < N) y[(int64_t)token * N + rr + i] = (_Float16)acc[r][t][i];
+            }
+        }
+}
+
+// y[i] = rne_fp16(partial[0][i] + partial[1][i] + ... ), summed in that order.
+__global__ __launch_bounds__(256) void gemm_reduce_kernel(const float* __restrict__ partial, int S, int64_t BN,
+                                                          _Float16* __restrict__ y) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= BN) return;
+    float sum = partial[i];
+    for (int s = 1; s < S; ++s) sum += partial[(int64_t)s * BN + i];
+    y[i] = (_Float16)sum;
+}
+
+// The split: (token groups, row groups per wave, waves per workgroup) by batch,
+// then as many splits of K as fill the compute units once.
+SplitPlan plan_split(int64_t N, int64_t K, int B) {
+    SplitPlan p;
+    p.tg = (B + 15) / 16;
+    p.rg = 1;
+    p.waves = 16;
+    const int64_t rows_per_group = 16 * p.rg * p.waves;
+    p.row_blocks = (N + rows_per_group - 1) / rows_per_group;
+    const int64_t windows = (K + kSkWindow - 1) / kSkWindow;
+    int64_t S = compute_units() / (p.row_blocks > 0 ? p.row_blocks : 1);
+    if (S < 1) S = 1;
+    if (S > windows) S = windows;
+    p.wps = (int)((windows + S - 1) / S);
+    p.splits = (int)((windows + p.wps - 1) / p.wps);
+    return p;
+}
+
+template <int TG, int RG, int W>
+static void launch_splitk(const SplitPlan& p, const uint8_t* packed, const uint8_t* q8, const float* scale2,
+                          const float* offset, const float* code2, int log2_bs, int64_t N, int64_t K,
+                          const _Float16* x, int B, float* partial, _Float16* y, hipStream_t s) {
+    hipLaunchKernelGGL((gemm_splitk_kernel<TG, RG, W>), dim3((unsigned)p.row_blocks, (unsigned)p.splits),
+                       dim3(W * kWave), 0, s, packed, q8, scale2, offset, code2, log2_bs, N, K, x, B, p.wps,
+                       p.splits > 1 ? partial : nullptr, y);
+}
+
+int launch_gemm_splitk(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
+                       const float* code2, int log2_bs, int64_t N, int64_t K, const _Float16* x, int B,
+                       _Float16* y, float* partial, hipStream_t s) {
+    const SplitPlan p = plan_split(N, K, B);
+#define NF4_SK_ARGS p, packed, q8, scale2, offset, code2, log2_bs, N, K, x, B, partial, y, s
+    switch (p.tg) {
+        case 1: launch_splitk<1, 1, 16>(NF4_SK_ARGS); break;
+        case 2: launch_splitk<2, 1, 16>(NF4_SK_ARGS); break;
+        case 3: launch_splitk<3, 1, 16>(NF4_SK_ARGS); break;
+        default: launch_splitk<4, 1, 16>(NF4_SK_ARGS); break;
+    }
+#undef NF4_SK_ARGS
+    int rc = record_hip(hipGetLastError());
+    if (rc != NF4_OK || p.splits == 1) return rc;
+    const int64_t BN = (int64_t)B * N;
+    hipLaunchKernelGGL(gemm_reduce_kernel, dim3((unsigned)((BN + 255) / 256)), dim3(256), 0, s, partial, p.splits,
+                       BN, y);
+    return record_hip(hipGetLastError());
+}
+
+}  // namespace nf4

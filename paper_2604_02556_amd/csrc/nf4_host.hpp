@@ -28,4 +28,18 @@ inline int log2_blocksize(int bs) {
 // Compute units of the current device (queried once per thread; 256 on MI355X).
 int compute_units();
 
+// How the split-K GEMM divides a problem: row blocks x splits workgroups, each
+// split taking `wps` windows of 256 k (nf4_gemm_splitk.hip).
+struct SplitPlan {
+    int tg, rg, waves;       // token groups, row groups per wave, waves per workgroup
+    int64_t row_blocks;
+    int wps, splits;
+};
+SplitPlan plan_split(int64_t N, int64_t K, int B);
+
+// Split-K GEMM: `partial` holds plan.splits * B * N floats when plan.splits > 1.
+int launch_gemm_splitk(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
+                       const float* code2, int log2_bs, int64_t N, int64_t K, const _Float16* x, int B,
+                       _Float16* y, float* partial, hipStream_t s);
+
 }  // namespace nf4

@@ -30,7 +30,7 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(L):
     names = declared_functions()
     assert set(names) >= {"nf4_dequantize", "nf4_dequantize_dq", "nf4_dequant_gemv", "nf4_quantize_ref",
-                          "nf4_quantize", "nf4_dequant_gemm", "nf4_last_hip_error", "nf4_status_string"}
+                          "nf4_quantize", "nf4_dequant_gemm", "nf4_dequant_gemm_workspace_bytes", "nf4_last_hip_error", "nf4_status_string"}
     for name in names:
         assert hasattr(L, name), name
 
@@ -92,15 +92,27 @@ def test_gemv_argument_checks(L):
 def test_gemm_argument_checks(L):
     f = L.nf4_dequant_gemm
     a = [P] * 5
-    assert f(*a, 64, -1, 64, P, 1, P, None) == E_SIZE
-    assert f(*a, 48, 4, 64, P, 1, P, None) == E_BS
-    assert f(*a, 64, 4, 64, P, 0, P, None) == E_SHAPE
-    assert f(*a, 64, 4, 64, P, 65, P, None) == E_SHAPE
-    assert f(*a, 64, 4, 96, P, 1, P, None) == E_SHAPE
-    assert f(*a, 64, 0, 64, P, 1, P, None) == OK
-    assert f(*a, 64, 4, 64, None, 1, P, None) == E_NULL
-    assert f(*a, 64, 4, 64, P, 1, None, None) == E_NULL
-    assert f(*a, 64, 4, 64, P + 2, 1, P, None) == E_ALIGN
+    for ws in ((None, 0), (P, 1 << 40)):
+        assert f(*a, 64, -1, 64, P, 1, P, *ws, None) == E_SIZE
+        assert f(*a, 48, 4, 64, P, 1, P, *ws, None) == E_BS
+        assert f(*a, 64, 4, 64, P, 0, P, *ws, None) == E_SHAPE
+        assert f(*a, 64, 4, 64, P, 65, P, *ws, None) == E_SHAPE
+        assert f(*a, 64, 4, 96, P, 1, P, *ws, None) == E_SHAPE
+        assert f(*a, 64, 0, 64, P, 1, P, *ws, None) == OK
+        assert f(*a, 64, 4, 64, None, 1, P, *ws, None) == E_NULL
+        assert f(*a, 64, 4, 64, P, 1, None, *ws, None) == E_NULL
+        assert f(*a, 64, 4, 64, P + 2, 1, P, *ws, None) == E_ALIGN
+    # a workspace that is misaligned or smaller than the split needs is refused before any launch
+    assert f(*a, 64, 4, 64, P, 1, P, P + 4, 1 << 40, None) == E_ALIGN
+    need = L.nf4_dequant_gemm_workspace_bytes(4096, 8192, 64)
+    assert need >= 2 * 64 * 4096 * 4                      # at least two splits of FP32 partial sums
+    assert f(*a, 64, 4096, 8192, P, 64, P, P, need - 1, None) == E_SIZE
+
+
+def test_gemm_workspace_bytes_of_rejected_shapes_is_zero(L):
+    g = L.nf4_dequant_gemm_workspace_bytes
+    assert g(0, 64, 1) == 0 and g(4, 0, 1) == 0 and g(4, 64, 0) == 0 and g(4, 64, 65) == 0
+    assert g(4, 64, 1) > 0
 
 
 def test_quantize_ref_argument_checks(L):

@@ -159,7 +159,7 @@ def test_config4_gemv_70b_mlp_shapes(N, K):
 
 
 @pytest.mark.parametrize("N,K", synth.GEMV_SHAPES)
-def test_gemm_70b_mlp_shapes_batches_16_and_64(N, K):
+def test_gemm_70b_mlp_shapes_both_algorithms(N, K):
     n = N * K
     w = draw(n, synth.LLAMA33_70B_SIGMA, 5000 + N % 7)
     bufs = nf4.alloc_quantized(n, dq=True)
@@ -169,11 +169,15 @@ def test_gemm_70b_mlp_shapes_batches_16_and_64(N, K):
     host = {k: v.cpu().numpy() for k, v in bufs.items()}
     rng = np.random.Generator(np.random.PCG64(N + K + 1))
     rows = np.unique(np.concatenate([np.arange(3), np.arange(N - 3, N), rng.integers(0, N, 10)]))
-    for B in (16, 64):
+    for B, split in ((16, False), (64, False), (16, True), (48, True), (64, True)):
         x = synth.activations_fp16(B, K, seed=5100 + B)
         y = torch.full((B, N), float("nan"), dtype=torch.float16, device="cuda")
+        ws = None
+        if split:
+            ws = torch.full((nf4.nf4_dequant_gemm_workspace_bytes(N, K, B) // 4,), float("nan"),
+                            dtype=torch.float32, device="cuda")
         nf4.nf4_dequant_gemm(bufs["packed"], bufs["absmax_q8"], bufs["scale2"], bufs["offset"], bufs["code2"], 64,
-                             N, K, torch.from_numpy(x).cuda(), B, y)
+                             N, K, torch.from_numpy(x).cuda(), B, y, workspace=ws)
         torch.cuda.synchronize()
         yh = y.cpu().numpy().astype(np.float64)
         assert np.isfinite(yh).all()
@@ -186,5 +190,5 @@ def test_gemm_70b_mlp_shapes_batches_16_and_64(N, K):
         rms = np.sqrt(np.mean(ref ** 2))
         assert np.all(np.abs(got - ref) <= 1e-2 * np.abs(ref) + 1e-2 * rms)
         rel = np.abs(got - ref).max() / np.abs(ref).max()
-        print(f"gemm N={N} K={K} B={B}: max err / max |y| = {rel:.2e}")
+        print(f"gemm N={N} K={K} B={B} split={split}: max err / max |y| = {rel:.2e}")
         assert rel < 2e-3
