@@ -45,6 +45,13 @@ def lib():
         L.nf4o_dequant_gemv_rows.restype = None
         L.nf4o_dequant_gemm_rows.argtypes = [vp, vp, vp, vp, vp, i32, i64, vp, i32, i64, i64, vp, vp]
         L.nf4o_dequant_gemm_rows.restype = None
+        L.nf4o_dequantize_codebook.argtypes = [vp, vp, vp, i32, i64, vp, i32]
+        L.nf4o_dequantize_dq_codebook.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, i64, vp, i32]
+        L.nf4o_quantize_codebook.argtypes = [vp, i64, i32, vp, vp, vp]
+        L.nf4o_dq_encode_group.argtypes = [vp, i64, i32, vp, vp, vp, vp]
+        for name in ("nf4o_dequantize_codebook", "nf4o_dequantize_dq_codebook", "nf4o_quantize_codebook",
+                     "nf4o_dq_encode_group"):
+            getattr(L, name).restype = None
         for name in ("nf4o_table", "nf4o_dequantize", "nf4o_dequantize_range", "nf4o_dq_decode",
                      "nf4o_dequantize_dq", "nf4o_quantize", "nf4o_dq_encode", "nf4o_dequant_gemv"):
             getattr(L, name).restype = None
@@ -206,3 +213,50 @@ def dequant_gemm_rows(packed, q8, scale2, offset, code2, N, K, x_bits, r_first, 
     lib().nf4o_dequant_gemm_rows(_p(packed), _p(q8), _p(scale2), _p(offset), _p(code2), blocksize, K,
                                  _p(x_bits), B, r_first, r_count, _p(y), _p(y64))
     return y, y64
+
+
+# ---- the data type as a parameter (Sec. V-A): any 16 levels, any second-level group size ----
+
+def quantize_codebook(src, codebook, blocksize=64):
+    src = _chk(src, np.float32).ravel()
+    codebook = _chk(codebook, np.float32, 16, "codebook")
+    n = src.size
+    packed = np.zeros((n + 1) // 2, dtype=np.uint8)
+    absmax = np.zeros(nblocks(n, blocksize), dtype=np.float32)
+    lib().nf4o_quantize_codebook(_p(src), n, blocksize, _p(codebook), _p(packed), _p(absmax))
+    return packed, absmax
+
+
+def dequantize_codebook(packed, absmax, codebook, n, blocksize=64, out_dtype=FP16):
+    packed = _chk(packed, np.uint8, (n + 1) // 2, "packed")
+    absmax = _chk(absmax, np.float32, nblocks(n, blocksize), "absmax")
+    codebook = _chk(codebook, np.float32, 16, "codebook")
+    out = _out(n, out_dtype)
+    lib().nf4o_dequantize_codebook(_p(packed), _p(absmax), _p(codebook), blocksize, n, _p(out), out_dtype)
+    return out
+
+
+def dq_encode_group(absmax, group):
+    """float32[nb] -> (q8 uint8[nb], scale2 float32[ceil(nb/group)], offset float32[1], code2 float32[256])."""
+    absmax = _chk(absmax, np.float32).ravel()
+    nb = absmax.size
+    q8 = np.zeros(nb, dtype=np.uint8)
+    scale2 = np.zeros((nb + group - 1) // group, dtype=np.float32)
+    offset = np.zeros(1, dtype=np.float32)
+    code2 = np.zeros(256, dtype=np.float32)
+    lib().nf4o_dq_encode_group(_p(absmax), nb, group, _p(q8), _p(scale2), _p(offset), _p(code2))
+    return q8, scale2, offset, code2
+
+
+def dequantize_dq_codebook(packed, q8, scale2, offset, code2, group, codebook, n, blocksize=64, out_dtype=FP16):
+    nb = nblocks(n, blocksize)
+    packed = _chk(packed, np.uint8, (n + 1) // 2, "packed")
+    q8 = _chk(q8, np.uint8, nb, "absmax_q8")
+    scale2 = _chk(scale2, np.float32, (nb + group - 1) // group, "scale2")
+    offset = _chk(offset, np.float32, 1, "offset")
+    code2 = _chk(code2, np.float32, 256, "code2")
+    codebook = _chk(codebook, np.float32, 16, "codebook")
+    out = _out(n, out_dtype)
+    lib().nf4o_dequantize_dq_codebook(_p(packed), _p(q8), _p(scale2), _p(offset), _p(code2), group, _p(codebook),
+                                      blocksize, n, _p(out), out_dtype)
+    return out

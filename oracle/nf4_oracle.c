@@ -27,8 +27,12 @@
  *     overflow to infinity, 0 * inf = NaN).
  *   - BF16 output, the double-quantised absmax and the fused GEMV are not in
  *     the paper; their definitions below are this build's statement of them.
- *     Parity unpinned (no external reference exists): nf4o_dq_encode.  Its
- *     decoder formula and invariants are pinned by tests.
+ *     Parity unpinned (no external reference exists): nf4o_dq_encode and its
+ *     group-size form nf4o_dq_encode_group.  Their decoder formula and
+ *     invariants are pinned by tests.
+ *   - Sec. V-A names the data type as a parameter of the kernel; the *_codebook
+ *     functions at the end state the same format for any table of 16 FP32
+ *     levels and any number of blocks per second-level group.
  *
  * Build: gcc -O2 -std=c99 -ffp-contract=off -fPIC -shared (no fast-math).
  */
@@ -307,6 +311,106 @@ void nf4o_dequant_gemm_rows(const uint8_t *packed, const uint8_t *absmax_q8, con
             int64_t o = (int64_t)b * r_count + (r - r_first);
             if (y_f64) y_f64[o] = acc;
             if (y) y[o] = nf4o_f32_to_f16((float)acc);
+        }
+    }
+}
+
+/* ---- the same format with the data type as a parameter (Sec. V-A) -------------
+ *
+ * `table` is any 16 FP32 levels, indexed by the 4-bit code; `group` is the number
+ * of quantisation blocks that share one second-level scale.  With the NF4 table
+ * and group = 256 these compute what the functions above compute. */
+
+void nf4o_dequantize_codebook(const uint8_t *packed, const float *absmax, const float *table,
+                              int blocksize, int64_t n, void *out, int out_dtype) {
+    for (int64_t i = 0; i < n; ++i) {
+        float level = table[code_of(packed, i)];
+        float scale = absmax[i / blocksize];
+        float v = level * scale;
+        store_out(out, i, v, out_dtype);
+    }
+}
+
+void nf4o_dequantize_dq_codebook(const uint8_t *packed, const uint8_t *absmax_q8,
+                                 const float *scale2, const float *offset, const float *code2,
+                                 int group, const float *table, int blocksize, int64_t n,
+                                 void *out, int out_dtype) {
+    for (int64_t i = 0; i < n; ++i) {
+        int64_t b = i / blocksize;
+        float prod = code2[absmax_q8[b]] * scale2[b / group];
+        float scale = prod + offset[0];
+        float level = table[code_of(packed, i)];
+        float v = level * scale;
+        store_out(out, i, v, out_dtype);
+    }
+}
+
+/* Nearest level of `table` to xn: smallest |xn - table[k]| in FP32, codes scanned
+ * from 0 upward with a strict comparison (a tie keeps the lower code). */
+static unsigned nearest_code(const float *table, float xn) {
+    unsigned best = 0;
+    float best_d = fabsf(xn - table[0]);
+    for (unsigned k = 1; k < 16; ++k) {
+        float d = fabsf(xn - table[k]);
+        if (d < best_d) { best_d = d; best = k; }
+    }
+    return best;
+}
+
+/* Forward direction for any table.  As nf4o_quantize, except that an all-zero
+ * block and the unused nibble of an odd n take the code nearest to 0 (for NF4
+ * that is code 7, the zero level). */
+void nf4o_quantize_codebook(const float *src, int64_t n, int blocksize, const float *table,
+                            uint8_t *packed, float *absmax) {
+    unsigned zero_code = nearest_code(table, 0.0f);
+    int64_t nb = (n + blocksize - 1) / blocksize;
+    for (int64_t b = 0; b < nb; ++b) {
+        int64_t lo = b * blocksize;
+        int64_t hi = lo + blocksize < n ? lo + blocksize : n;
+        float a = 0.0f;
+        for (int64_t i = lo; i < hi; ++i) {
+            float m = fabsf(src[i]);
+            if (m > a) a = m;
+        }
+        absmax[b] = a;
+        for (int64_t i = lo; i < hi; ++i) {
+            unsigned best = a != 0.0f ? nearest_code(table, src[i] / a) : zero_code;
+            uint8_t *byte = &packed[i >> 1];
+            if ((i & 1) == 0) *byte = (uint8_t)((best << 4) | zero_code);
+            else *byte = (uint8_t)((*byte & 0xF0u) | best);
+        }
+    }
+}
+
+/* nf4o_dq_encode with `group` blocks per second-level scale instead of 256. */
+void nf4o_dq_encode_group(const float *absmax, int64_t nb, int group, uint8_t *absmax_q8,
+                          float *scale2, float *offset, float *code2) {
+    for (int u = 0; u < 256; ++u) code2[u] = (float)(u - 127) / 127.0f;
+    double sum = 0.0;
+    for (int64_t b = 0; b < nb; ++b) sum += (double)absmax[b];
+    float off = nb > 0 ? (float)(sum / (double)nb) : 0.0f;
+    offset[0] = off;
+    int64_t ng = (nb + group - 1) / group;
+    for (int64_t g = 0; g < ng; ++g) {
+        int64_t lo = g * group;
+        int64_t hi = lo + group < nb ? lo + group : nb;
+        float s = 0.0f;
+        for (int64_t b = lo; b < hi; ++b) {
+            float d = fabsf(absmax[b] - off);
+            if (d > s) s = d;
+        }
+        scale2[g] = s;
+        for (int64_t b = lo; b < hi; ++b) {
+            int q = 127;
+            if (s != 0.0f) {
+                float centred = absmax[b] - off;
+                float scaled = 127.0f * centred;
+                float r = rintf(scaled / s);
+                if (r < -127.0f) r = -127.0f;
+                if (r > 127.0f) r = 127.0f;
+                q = 127 + (int)r;
+            }
+            absmax_q8[b] = (uint8_t)q;
         }
     }
 }

@@ -35,6 +35,14 @@ MUTATIONS = [
     ("gemm weight not rounded to fp16", "double w16 = f16_bits_to_double(nf4o_f32_to_f16(w));", "double w16 = (double)w;"),
     ("gemv weight rounded to fp16 first", "acc += f16_bits_to_double(x[(int64_t)b * K + k]) * (double)w;",
      "acc += f16_bits_to_double(x[(int64_t)b * K + k]) * f16_bits_to_double(nf4o_f32_to_f16(w));"),
+    ("codebook form ignores its table", "float level = table[code_of(packed, i)];\n        float scale = absmax[i / blocksize];",
+     "float level = NF4_LEVEL[code_of(packed, i)];\n        float scale = absmax[i / blocksize];"),
+    ("codebook double-quant form uses groups of 256", "float prod = code2[absmax_q8[b]] * scale2[b / group];",
+     "float prod = code2[absmax_q8[b]] * scale2[b / 256];"),
+    ("codebook quantiser ties go to the upper code", "float d = fabsf(xn - table[k]);\n        if (d < best_d) { best_d = d; best = k; }",
+     "float d = fabsf(xn - table[k]);\n        if (d <= best_d) { best_d = d; best = k; }"),
+    ("codebook quantiser zero code fixed at 7", "unsigned zero_code = nearest_code(table, 0.0f);", "unsigned zero_code = 7;"),
+    ("group encoder strides by 256", "int64_t lo = g * group;", "int64_t lo = g * 256;"),
 ]
 
 

@@ -392,3 +392,122 @@ def test_gemm_equals_float64_matmul_of_fp16_dequantized_weights():
     # and it differs from the unrounded GEMV where rounding the weights matters
     _, y_exact = oracle.dequant_gemv(p, q8, s2, off, c2, N, K, x.view(np.uint16))
     assert not np.array_equal(y_exact, y64) and np.allclose(y_exact, y64, rtol=0, atol=2e-3 * np.abs(y64).max())
+
+
+# ---------------------------------------------- the data type as a parameter (Sec. V-A)
+
+def e2m1_codebook():
+    """The 4-bit float of the OCP microscaling format family (1 sign, 2 exponent, 1 mantissa bit), decoded
+    from its definition and normalised to [-1, 1]: code = s e e m; e = 0 is subnormal (m / 2), else
+    (1 + m / 2) * 2^(e - 1)."""
+    vals = []
+    for code in range(16):
+        s, e, m = code >> 3, (code >> 1) & 3, code & 1
+        mag = 0.5 * m if e == 0 else (1.0 + 0.5 * m) * 2.0 ** (e - 1)
+        vals.append(-mag if s else mag)
+    return (np.array(vals, dtype=np.float64) / 6.0).astype(np.float32)
+
+
+def test_e2m1_codebook_is_the_published_value_set():
+    t = e2m1_codebook().astype(np.float64) * 6.0
+    assert np.allclose(t[:8], [0, 0.5, 1, 1.5, 2, 3, 4, 6], atol=1e-6) and np.allclose(t[8:], -t[:8], atol=1e-6)
+    assert np.signbit(e2m1_codebook()[8]) and not np.signbit(e2m1_codebook()[0])      # -0 and +0 are two codes
+
+
+def test_codebook_functions_with_the_nf4_table_are_the_nf4_functions():
+    rng = np.random.Generator(np.random.PCG64(41))
+    n = 64 * 300 + 37
+    w = (rng.standard_normal(n) * 0.02).astype(np.float32)
+    t = oracle.table()
+    p, a = oracle.quantize(w)
+    p2, a2 = oracle.quantize_codebook(w, t)
+    assert np.array_equal(p, p2) and np.array_equal(a.view(np.uint32), a2.view(np.uint32))
+    for dt in (oracle.FP16, oracle.BF16, oracle.FP32):
+        assert np.array_equal(oracle.dequantize(p, a, n, out_dtype=dt).view(np.uint8),
+                              oracle.dequantize_codebook(p, a, t, n, out_dtype=dt).view(np.uint8))
+    dq = oracle.dq_encode(a)
+    dq2 = oracle.dq_encode_group(a, 256)
+    for x, y in zip(dq, dq2):
+        assert np.array_equal(x.view(np.uint8), y.view(np.uint8))
+    assert np.array_equal(oracle.dequantize_dq(p, *dq, n, out_dtype=oracle.BF16),
+                          oracle.dequantize_dq_codebook(p, *dq, 256, t, n, out_dtype=oracle.BF16))
+
+
+def test_codebook_dequantize_with_a_counting_table_returns_the_codes():
+    # table[i] = i and scale 1: the output IS the code sequence, high nibble first (Algorithm 1),
+    # whatever the NF4 levels are
+    rng = np.random.Generator(np.random.PCG64(42))
+    n = 1001
+    packed = rng.integers(0, 256, (n + 1) // 2, dtype=np.uint8)
+    counting = np.arange(16, dtype=np.float32)
+    out = oracle.dequantize_codebook(packed, np.ones(oracle.nblocks(n), np.float32), counting, n, out_dtype=oracle.FP32)
+    codes = np.stack([packed >> 4, packed & 15], axis=1).ravel()[:n]
+    assert np.array_equal(out, codes.astype(np.float32))
+    # and with per-block scales 2^b (exact products): block b of 128 elements is scaled by its own entry
+    scales = (2.0 ** (np.arange(oracle.nblocks(n, 128)) % 5)).astype(np.float32)
+    out = oracle.dequantize_codebook(packed, scales, counting, n, blocksize=128, out_dtype=oracle.FP32)
+    assert np.array_equal(out, codes.astype(np.float32) * np.repeat(scales, 128)[:n])
+
+
+def test_codebook_quantize_is_brute_force_nearest_with_ties_to_the_lower_code():
+    t = e2m1_codebook()
+    rng = np.random.Generator(np.random.PCG64(43))
+    n = 64 * 40
+    w = (rng.standard_normal(n) * 0.3).astype(np.float32)
+    w[5] = 0.0                                     # +0 / -0 levels tie: the lower code (0) wins
+    w[64:128] = 0.0                                # an all-zero block
+    # exact midpoints between neighbouring levels (1/12 between 0 and 1/12 ... in a block with absmax 1)
+    w[128] = 1.0
+    w[129:133] = [1.0 / 24, 3.0 / 24, 0.75, -0.75]
+    p, a = oracle.quantize_codebook(w, t)
+    codes = np.stack([p >> 4, p & 15], axis=1).ravel()[:n]
+    blocks = w.reshape(-1, 64)
+    amax = np.abs(blocks).max(axis=1)
+    assert np.array_equal(a, amax)
+    safe = np.where(amax == 0, np.float32(1), amax)[:, None]
+    xn = (blocks / safe).astype(np.float32)
+    dist = np.abs(xn[:, :, None] - t[None, None, :]).astype(np.float32)
+    brute = dist.argmin(axis=2).ravel()            # numpy's argmin returns the first minimum
+    assert np.array_equal(codes, brute)
+    assert codes[5] == 0 and np.all(codes[64:128] == 0)
+    # odd n: the unused nibble holds the code nearest to zero (for this table code 0, for NF4 code 7)
+    p_odd, _ = oracle.quantize_codebook(w[:7], t)
+    assert p_odd[3] & 15 == 0
+    p_nf4, _ = oracle.quantize_codebook(w[:7], oracle.table())
+    assert p_nf4[3] & 15 == 7
+
+
+@pytest.mark.parametrize("group", [1, 16, 64, 256, 1024])
+def test_dq_encode_group_sizes(group):
+    rng = np.random.Generator(np.random.PCG64(44 + group))
+    nb = 3 * 1024 + 77
+    a = np.abs(rng.standard_normal(nb) * 0.01 + 0.05).astype(np.float32)
+    q8, s2, off, c2 = oracle.dq_encode_group(a, group)
+    ng = (nb + group - 1) // group
+    assert s2.size == ng and q8.size == nb
+    assert off[0] == np.float32(a.astype(np.float64).sum() / nb)
+    pad = np.full(ng * group - nb, off[0], np.float32)
+    centred = np.abs(np.concatenate([a, pad]) - off[0]).astype(np.float32).reshape(ng, group)
+    assert np.array_equal(s2, centred.max(axis=1))                           # each group has its own scale
+    # decoder formula (two separately rounded FP32 operations) and its error bound of half a code step
+    dec = (c2[q8] * np.repeat(s2, group)[:nb]).astype(np.float32) + off[0]
+    bound = np.repeat(s2, group)[:nb].astype(np.float64) / 254.0 + 1e-7
+    assert np.all(np.abs(dec.astype(np.float64) - a) <= bound)
+    if group == 1:                                                           # closed form: every block is its own extreme
+        assert set(np.unique(q8)) <= {0, 127, 254}
+        assert np.array_equal(q8 == 254, a > off[0])
+
+
+def test_dequantize_dq_codebook_equals_decode_then_dequantize():
+    rng = np.random.Generator(np.random.PCG64(45))
+    t = e2m1_codebook()
+    n = 128 * 70 + 5
+    w = (rng.standard_normal(n) * 0.02).astype(np.float32)
+    p, a = oracle.quantize_codebook(w, t, blocksize=128)
+    for group in (16, 64):
+        q8, s2, off, c2 = oracle.dq_encode_group(a, group)
+        dec = (c2[q8] * np.repeat(s2, group)[:a.size]).astype(np.float32) + off[0]
+        for dt in (oracle.FP16, oracle.BF16):
+            want = oracle.dequantize_codebook(p, dec, t, n, blocksize=128, out_dtype=dt)
+            got = oracle.dequantize_dq_codebook(p, q8, s2, off, c2, group, t, n, blocksize=128, out_dtype=dt)
+            assert np.array_equal(want, got)
