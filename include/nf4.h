@@ -125,6 +125,22 @@ int nf4_dequant_gemm(const uint8_t* packed, const uint8_t* absmax_q8, const floa
 size_t nf4_dequant_gemm_workspace_bytes(int64_t N, int64_t K, int B);
 
 /*
+ * The same format with the data type as a parameter (Sec. V-A names it as one of
+ * the kernel's parameters): `codebook` is any 16 FP32 levels indexed by the 4-bit
+ * code (device, 4-byte aligned; NULL = the NF4 levels), `dq_group` the number of
+ * quantisation blocks per second-level scale (a power of two in [1, 65536], else
+ * NF4_ERR_SHAPE; scale2 then holds ceil(nb / dq_group) floats).  Everything else
+ * as in nf4_dequantize / nf4_dequantize_dq, which are these calls with NULL and
+ * 256.  out[i] = rne16(codebook[code_i] * scale(i / blocksize)).
+ */
+int nf4_dequantize_codebook(const uint8_t* packed, const float* absmax, const float* codebook,
+                            int blocksize, int64_t n, void* out, int out_dtype, void* stream);
+int nf4_dequantize_dq_codebook(const uint8_t* packed, const uint8_t* absmax_q8, const float* scale2,
+                               const float* offset, const float* code2, int dq_group,
+                               const float* codebook, int blocksize, int64_t n, void* out,
+                               int out_dtype, void* stream);
+
+/*
  * Reference-quality (untuned) quantiser, the forward direction of Sec. II-B:
  * per block absmax = max |src|, code = nearest level to src / absmax (FP32
  * distance, ties to the lower index, all-zero block -> absmax 0 and code 7,
@@ -138,6 +154,17 @@ size_t nf4_dequant_gemm_workspace_bytes(int64_t N, int64_t K, int B);
 int nf4_quantize_ref(const float* src, int64_t n, int blocksize, uint8_t* packed, float* absmax,
                      uint8_t* absmax_q8, float* scale2, float* offset, float* code2,
                      void* stream);
+
+/*
+ * nf4_quantize_ref for any codebook and second-level group size (see
+ * nf4_dequantize_codebook for both arguments).  Nearest level = smallest
+ * |x / absmax - codebook[k]| in FP32, codes scanned from 0 upward, a tie keeps the
+ * lower code; an all-zero block and the unused nibble of an odd n take the code
+ * nearest to 0.  dq_group is only read when absmax_q8 != NULL.
+ */
+int nf4_quantize_ref_codebook(const float* src, int64_t n, int blocksize, const float* codebook,
+                              int dq_group, uint8_t* packed, float* absmax, uint8_t* absmax_q8,
+                              float* scale2, float* offset, float* code2, void* stream);
 
 /*
  * Tuned quantiser, first level only (Sec. II-B, forward direction): writes

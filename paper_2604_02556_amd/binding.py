@@ -43,6 +43,11 @@ def lib():
     L.nf4_dequant_gemm_workspace_bytes.argtypes = [i64, i64, i32]
     L.nf4_dequant_gemm_workspace_bytes.restype = c.c_size_t
     L.nf4_quantize_ref.argtypes = [vp, i64, i32, vp, vp, vp, vp, vp, vp, vp]
+    L.nf4_dequantize_codebook.argtypes = [vp, vp, vp, i32, i64, vp, i32, vp]
+    L.nf4_dequantize_dq_codebook.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, i64, vp, i32, vp]
+    L.nf4_quantize_ref_codebook.argtypes = [vp, i64, i32, vp, i32, vp, vp, vp, vp, vp, vp, vp]
+    for f in (L.nf4_dequantize_codebook, L.nf4_dequantize_dq_codebook, L.nf4_quantize_ref_codebook):
+        f.restype = i32
     L.nf4_quantize.argtypes = [vp, i64, i32, vp, vp, vp]
     for f in (L.nf4_dequantize, L.nf4_dequantize_dq, L.nf4_dequant_gemv, L.nf4_quantize_ref, L.nf4_quantize,
               L.nf4_last_hip_error):
@@ -96,6 +101,28 @@ def nf4_dequantize_dq(packed, absmax_q8, scale2, offset, code2, blocksize, n, ou
     return out
 
 
+def nf4_dequantize_codebook(packed, absmax, codebook, blocksize, n, out, stream=None):
+    """nf4_dequantize with the caller's 16 levels (a float32 device tensor; None = NF4)."""
+    _check(lib().nf4_dequantize_codebook(_ptr(packed), _ptr(absmax), _ptr(codebook), blocksize, n, _ptr(out),
+                                         _DTYPE_CODE[out.dtype], _stream(stream)))
+    return out
+
+
+def nf4_dequantize_dq_codebook(packed, absmax_q8, scale2, offset, code2, dq_group, codebook, blocksize, n, out,
+                               stream=None):
+    _check(lib().nf4_dequantize_dq_codebook(_ptr(packed), _ptr(absmax_q8), _ptr(scale2), _ptr(offset), _ptr(code2),
+                                            dq_group, _ptr(codebook), blocksize, n, _ptr(out),
+                                            _DTYPE_CODE[out.dtype], _stream(stream)))
+    return out
+
+
+def nf4_quantize_ref_codebook(src, n, blocksize, codebook, dq_group, packed, absmax, absmax_q8=None, scale2=None,
+                              offset=None, code2=None, stream=None):
+    _check(lib().nf4_quantize_ref_codebook(_ptr(src), n, blocksize, _ptr(codebook), dq_group, _ptr(packed),
+                                           _ptr(absmax), _ptr(absmax_q8), _ptr(scale2), _ptr(offset), _ptr(code2),
+                                           _stream(stream)))
+
+
 def nf4_dequant_gemv(packed, absmax_q8, scale2, offset, code2, blocksize, N, K, x, B, y, stream=None):
     _check(lib().nf4_dequant_gemv(_ptr(packed), _ptr(absmax_q8), _ptr(scale2), _ptr(offset), _ptr(code2),
                                   blocksize, N, K, _ptr(x), B, _ptr(y), _stream(stream)))
@@ -128,7 +155,7 @@ def nf4_quantize(src, n, blocksize, packed, absmax, stream=None):
 
 # ---- allocation helpers (plumbing only: sizes of the format's arrays) ----
 
-def alloc_quantized(n, blocksize=64, dq=False, device="cuda"):
+def alloc_quantized(n, blocksize=64, dq=False, device="cuda", dq_group=256):
     """Empty device buffers for a tensor of n elements: dict of packed, absmax and (dq) q8/scale2/offset/code2."""
     nb = (n + blocksize - 1) // blocksize
     bufs = {
@@ -137,7 +164,7 @@ def alloc_quantized(n, blocksize=64, dq=False, device="cuda"):
     }
     if dq:
         bufs["absmax_q8"] = torch.empty(max(nb, 1), dtype=torch.uint8, device=device)
-        bufs["scale2"] = torch.empty(max((nb + 255) // 256, 1), dtype=torch.float32, device=device)
+        bufs["scale2"] = torch.empty(max((nb + dq_group - 1) // dq_group, 1), dtype=torch.float32, device=device)
         bufs["offset"] = torch.empty(1, dtype=torch.float32, device=device)
         bufs["code2"] = torch.empty(256, dtype=torch.float32, device=device)
     return bufs

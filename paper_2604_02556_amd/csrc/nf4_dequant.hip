@@ -49,6 +49,8 @@ struct ScaleArgs {
     const float* scale2;
     const float* offset;
     const float* code2;
+    int log2_group;          // blocks per second-level scale (8 = the format's 256)
+    const float* codebook;   // 16 levels in memory, or nullptr for the NF4 literals
 };
 
 // Eight codes of one dword -> eight scaled 16-bit values.  Byte j of the dword
@@ -68,7 +70,7 @@ __device__ __forceinline__ u32x4 expand8(uint32_t q, float s, const float* lut) 
 // Double-quantised scale of block `blk`: a rounded product, then a rounded sum
 // (never an FMA).
 __device__ __forceinline__ float dq_scale(const ScaleArgs& a, float offset, int64_t blk) {
-    const float prod = a.code2[a.q8[blk]] * a.scale2[blk >> 8];
+    const float prod = a.code2[a.q8[blk]] * a.scale2[blk >> a.log2_group];
     return prod + offset;
 }
 
@@ -81,7 +83,9 @@ __global__ __launch_bounds__(kWave) void dequant_kernel(const uint8_t* __restric
     const int lane = threadIdx.x;
     const int64_t t = blockIdx.x;
     const float offset = DQ ? sa.offset[0] : 0.0f;
-    if (lane < 16) lut[lane] = __uint_as_float(level_literal(lane));   // ordered by the fence below
+    // the table: instruction literals for NF4, 64 bytes from memory for a caller's codebook (Sec. V-A: the
+    // data type is a parameter); either way ordered by the fence below
+    if (lane < 16) lut[lane] = sa.codebook ? sa.codebook[lane] : __uint_as_float(level_literal(lane));
 
     if (t < tiles) {
         const int64_t e0 = t * kTileElems;
@@ -144,6 +148,7 @@ template <bool DQ>
 static int launch(const uint8_t* packed, const ScaleArgs& sa, int blocksize, int64_t n, void* out,
                   int out_dtype, void* stream) {
     if (n < 0) return NF4_ERR_SIZE;
+    if (sa.codebook && !aligned(sa.codebook, 4)) return NF4_ERR_ALIGN;
     const int log2_bs = log2_blocksize(blocksize);
     if (log2_bs < 0) return NF4_ERR_BLOCKSIZE;
     if (out_dtype != NF4_FP16 && out_dtype != NF4_BF16) return NF4_ERR_DTYPE;
@@ -176,13 +181,29 @@ static int launch(const uint8_t* packed, const ScaleArgs& sa, int blocksize, int
 
 extern "C" int nf4_dequantize(const uint8_t* packed, const float* absmax, int blocksize, int64_t n,
                               void* out, int out_dtype, void* stream) {
-    nf4::ScaleArgs sa = {absmax, nullptr, nullptr, nullptr, nullptr};
+    nf4::ScaleArgs sa = {absmax, nullptr, nullptr, nullptr, nullptr, 8, nullptr};
+    return nf4::launch<false>(packed, sa, blocksize, n, out, out_dtype, stream);
+}
+
+extern "C" int nf4_dequantize_codebook(const uint8_t* packed, const float* absmax, const float* codebook,
+                                       int blocksize, int64_t n, void* out, int out_dtype, void* stream) {
+    nf4::ScaleArgs sa = {absmax, nullptr, nullptr, nullptr, nullptr, 8, codebook};
     return nf4::launch<false>(packed, sa, blocksize, n, out, out_dtype, stream);
 }
 
 extern "C" int nf4_dequantize_dq(const uint8_t* packed, const uint8_t* absmax_q8, const float* scale2,
                                  const float* offset, const float* code2, int blocksize, int64_t n,
                                  void* out, int out_dtype, void* stream) {
-    nf4::ScaleArgs sa = {nullptr, absmax_q8, scale2, offset, code2};
+    nf4::ScaleArgs sa = {nullptr, absmax_q8, scale2, offset, code2, 8, nullptr};
+    return nf4::launch<true>(packed, sa, blocksize, n, out, out_dtype, stream);
+}
+
+extern "C" int nf4_dequantize_dq_codebook(const uint8_t* packed, const uint8_t* absmax_q8, const float* scale2,
+                                          const float* offset, const float* code2, int dq_group,
+                                          const float* codebook, int blocksize, int64_t n, void* out,
+                                          int out_dtype, void* stream) {
+    const int log2_group = nf4::log2_dq_group(dq_group);
+    if (log2_group < 0) return NF4_ERR_SHAPE;
+    nf4::ScaleArgs sa = {nullptr, absmax_q8, scale2, offset, code2, log2_group, codebook};
     return nf4::launch<true>(packed, sa, blocksize, n, out, out_dtype, stream);
 }

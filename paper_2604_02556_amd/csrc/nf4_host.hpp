@@ -25,6 +25,13 @@ inline int log2_blocksize(int bs) {
     return -1;
 }
 
+// log2(group) for a power of two in [1, 65536] blocks per second-level scale, else -1.
+inline int log2_dq_group(int group) {
+    for (int s = 0; s <= 16; ++s)
+        if (group == (1 << s)) return s;
+    return -1;
+}
+
 // Compute units of the current device (queried once per thread; 256 on MI355X).
 int compute_units();
 

@@ -183,8 +183,8 @@ __global__ __launch_bounds__(kWave) void quantize_tiles_kernel(const float* __re
 }
 
 // the reference kernel (nf4_quantize_ref.hip) finishes what does not fill a tile
-int launch_quantize_ref_range(const float* src, int64_t n, int blocksize, uint8_t* packed, float* absmax,
-                              hipStream_t s);
+int launch_quantize_ref_range(const float* src, int64_t n, int blocksize, const float* codebook, uint8_t* packed,
+                              float* absmax, hipStream_t s);
 
 }  // namespace nf4
 
@@ -198,7 +198,7 @@ extern "C" int nf4_quantize(const float* src, int64_t n, int blocksize, uint8_t*
     if (!aligned(src, 16) || !aligned(absmax, 4) || !aligned(packed, 2)) return NF4_ERR_ALIGN;
     hipStream_t s = (hipStream_t)stream;
     const QuantBins* qb = quant_bins();
-    if (blocksize != 64 || qb == nullptr) return launch_quantize_ref_range(src, n, blocksize, packed, absmax, s);
+    if (blocksize != 64 || qb == nullptr) return launch_quantize_ref_range(src, n, blocksize, nullptr, packed, absmax, s);
 
     const int64_t tiles = n / kQTileElems;
     if (tiles > 0x7fffffffLL) return NF4_ERR_SIZE;
@@ -209,5 +209,5 @@ extern "C" int nf4_quantize(const float* src, int64_t n, int blocksize, uint8_t*
     }
     const int64_t done = tiles * kQTileElems;
     if (done == n) return NF4_OK;
-    return launch_quantize_ref_range(src + done, n - done, 64, packed + done / 2, absmax + done / 64, s);
+    return launch_quantize_ref_range(src + done, n - done, 64, nullptr, packed + done / 2, absmax + done / 64, s);
 }

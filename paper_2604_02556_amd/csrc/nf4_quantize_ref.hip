@@ -20,16 +20,33 @@ __device__ __forceinline__ float wave_max(float v) {
     return v;
 }
 
+// Nearest of the 16 levels: smallest |xn - level| in FP32, codes scanned upward, strict comparison (a tie
+// keeps the lower code).
+__device__ __forceinline__ unsigned nearest_code(const float* lut, float xn) {
+    float best_d = fabsf(xn - lut[0]);
+    unsigned best = 0;
+#pragma unroll
+    for (unsigned k = 1; k < 16; ++k) {
+        float d = fabsf(xn - lut[k]);
+        if (d < best_d) { best_d = d; best = k; }
+    }
+    return best;
+}
+
 // One wave per quantisation block.  Pass 1: absmax.  Pass 2: for every pair of
 // elements the even lane gathers its neighbour's code and writes the byte
-// (element 2j in the high nibble).
+// (element 2j in the high nibble).  `codebook` is the caller's 16 levels, or
+// nullptr for NF4; an all-zero block and the unused nibble of an odd n take the
+// code nearest to zero (7 for NF4).
 __global__ __launch_bounds__(kQThreads) void quantize_kernel(const float* __restrict__ src, int64_t n,
                                                              int blocksize, int64_t nb,
+                                                             const float* __restrict__ codebook,
                                                              uint8_t* __restrict__ packed,
                                                              float* __restrict__ absmax) {
     __shared__ float lut[16];
-    if (threadIdx.x < 16) lut[threadIdx.x] = __uint_as_float(kLevelBits[threadIdx.x]);
+    if (threadIdx.x < 16) lut[threadIdx.x] = codebook ? codebook[threadIdx.x] : __uint_as_float(kLevelBits[threadIdx.x]);
     __syncthreads();
+    const unsigned zero_code = nearest_code(lut, 0.0f);
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t stride = (int64_t)gridDim.x * kQWaves;
     for (int64_t b = (int64_t)blockIdx.x * kQWaves + (threadIdx.x >> 6); b < nb; b += stride) {
@@ -44,19 +61,10 @@ __global__ __launch_bounds__(kQThreads) void quantize_kernel(const float* __rest
         if (lane == 0) absmax[b] = a;
         for (int64_t i0 = lo; i0 < hi; i0 += kWave) {      // uniform trip count: shuffles stay converged
             const int64_t i = i0 + lane;
-            unsigned best = 7;
-            if (i < hi && a != 0.0f) {
-                const float xn = src[i] / a;               // IEEE division
-                float best_d = fabsf(xn - lut[0]);
-                best = 0;
-#pragma unroll
-                for (unsigned k = 1; k < 16; ++k) {
-                    float d = fabsf(xn - lut[k]);
-                    if (d < best_d) { best_d = d; best = k; }   // strict: ties keep the lower index
-                }
-            }
-            const unsigned next = __shfl_down(best, 1, kWave); // code of element i + 1 (7 if absent)
-            if ((lane & 1) == 0 && i < hi) packed[i >> 1] = (uint8_t)((best << 4) | (i + 1 < hi ? next : 7u));
+            unsigned best = zero_code;
+            if (i < hi && a != 0.0f) best = nearest_code(lut, src[i] / a);   // IEEE division
+            const unsigned next = __shfl_down(best, 1, kWave); // code of element i + 1
+            if ((lane & 1) == 0 && i < hi) packed[i >> 1] = (uint8_t)((best << 4) | (i + 1 < hi ? next : zero_code));
         }
     }
 }
@@ -82,17 +90,18 @@ __global__ __launch_bounds__(kWave) void dq_offset_kernel(const float* __restric
     if (threadIdx.x == 0) offset[0] = (float)(sum / (double)nb);
 }
 
-// One wave per group of 256 first-level scales.
+// One wave per group of `group` first-level scales (256 in the format's default).
 __global__ __launch_bounds__(kQThreads) void dq_encode_kernel(const float* __restrict__ absmax, int64_t nb,
-                                                              int64_t ng, const float* __restrict__ offset,
+                                                              int64_t ng, int64_t group,
+                                                              const float* __restrict__ offset,
                                                               uint8_t* __restrict__ q8,
                                                               float* __restrict__ scale2) {
     const int lane = threadIdx.x & (kWave - 1);
     const float off = offset[0];
     const int64_t stride = (int64_t)gridDim.x * kQWaves;
     for (int64_t g = (int64_t)blockIdx.x * kQWaves + (threadIdx.x >> 6); g < ng; g += stride) {
-        const int64_t lo = g * 256;
-        const int64_t hi = lo + 256 < nb ? lo + 256 : nb;
+        const int64_t lo = g * group;
+        const int64_t hi = lo + group < nb ? lo + group : nb;
         float s = 0.0f;
         for (int64_t b = lo + lane; b < hi; b += kWave) {
             float d = fabsf(absmax[b] - off);
@@ -117,45 +126,53 @@ __global__ __launch_bounds__(kQThreads) void dq_encode_kernel(const float* __res
 
 // First level only (codes and absmax) of a range that starts on a block boundary;
 // also used by the tuned quantiser for other block sizes and for ragged ends.
-int launch_quantize_ref_range(const float* src, int64_t n, int blocksize, uint8_t* packed, float* absmax,
-                              hipStream_t s) {
+int launch_quantize_ref_range(const float* src, int64_t n, int blocksize, const float* codebook, uint8_t* packed,
+                              float* absmax, hipStream_t s) {
     const int64_t nb = (n + blocksize - 1) / blocksize;
     const int64_t cap = (int64_t)compute_units() * 16;
     int64_t groups = (nb + kQWaves - 1) / kQWaves;
     groups = groups < cap ? groups : cap;
     hipLaunchKernelGGL(quantize_kernel, dim3((unsigned)groups), dim3(kQThreads), 0, s, src, n, blocksize, nb,
-                       packed, absmax);
+                       codebook, packed, absmax);
     return record_hip(hipGetLastError());
 }
 
 }  // namespace nf4
 
-extern "C" int nf4_quantize_ref(const float* src, int64_t n, int blocksize, uint8_t* packed, float* absmax,
-                                uint8_t* absmax_q8, float* scale2, float* offset, float* code2,
-                                void* stream) {
+extern "C" int nf4_quantize_ref_codebook(const float* src, int64_t n, int blocksize, const float* codebook,
+                                         int dq_group, uint8_t* packed, float* absmax, uint8_t* absmax_q8,
+                                         float* scale2, float* offset, float* code2, void* stream) {
     using namespace nf4;
     if (n < 0) return NF4_ERR_SIZE;
     if (log2_blocksize(blocksize) < 0) return NF4_ERR_BLOCKSIZE;
+    const bool dq = absmax_q8 != nullptr;
+    if (dq && log2_dq_group(dq_group) < 0) return NF4_ERR_SHAPE;
     if (n == 0) return NF4_OK;
     if (!src || !packed || !absmax) return NF4_ERR_NULL;
-    const bool dq = absmax_q8 != nullptr;
     if (dq && (!scale2 || !offset || !code2)) return NF4_ERR_NULL;
-    if (!aligned(src, 4) || !aligned(absmax, 4)) return NF4_ERR_ALIGN;
+    if (!aligned(src, 4) || !aligned(absmax, 4) || (codebook && !aligned(codebook, 4))) return NF4_ERR_ALIGN;
     if (dq && (!aligned(scale2, 4) || !aligned(offset, 4) || !aligned(code2, 4))) return NF4_ERR_ALIGN;
 
     hipStream_t s = (hipStream_t)stream;
     const int64_t nb = (n + blocksize - 1) / blocksize;
     const int64_t cap = (int64_t)compute_units() * 16;
-    int rc = launch_quantize_ref_range(src, n, blocksize, packed, absmax, s);
+    int rc = launch_quantize_ref_range(src, n, blocksize, codebook, packed, absmax, s);
     if (rc != NF4_OK || !dq) return rc;
 
-    const int64_t ng = (nb + 255) / 256;
+    const int64_t ng = (nb + dq_group - 1) / dq_group;
     hipLaunchKernelGGL(dq_offset_kernel, dim3(1), dim3(kWave), 0, s, (const float*)absmax, nb, offset, code2);
     rc = record_hip(hipGetLastError());
     if (rc != NF4_OK) return rc;
     int64_t g2 = (ng + kQWaves - 1) / kQWaves;
     g2 = g2 < cap ? g2 : cap;
     hipLaunchKernelGGL(dq_encode_kernel, dim3((unsigned)g2), dim3(kQThreads), 0, s, (const float*)absmax, nb, ng,
-                       (const float*)offset, absmax_q8, scale2);
+                       (int64_t)dq_group, (const float*)offset, absmax_q8, scale2);
     return record_hip(hipGetLastError());
+}
+
+extern "C" int nf4_quantize_ref(const float* src, int64_t n, int blocksize, uint8_t* packed, float* absmax,
+                                uint8_t* absmax_q8, float* scale2, float* offset, float* code2,
+                                void* stream) {
+    return nf4_quantize_ref_codebook(src, n, blocksize, nullptr, 256, packed, absmax, absmax_q8, scale2, offset,
+                                     code2, stream);
 }

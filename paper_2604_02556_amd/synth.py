@@ -70,3 +70,10 @@ def positive_scales(count, seed, lo=1e-3, hi=1.0):
     """float32[count] log-uniform in [lo, hi): stand-in absmax values."""
     rng = np.random.Generator(np.random.PCG64(seed))
     return np.exp(rng.uniform(np.log(lo), np.log(hi), size=count)).astype(np.float32)
+
+
+def e2m1_codebook():
+    """An FP4-style alternative to the NF4 levels, as input data for the codebook entry points: the 16 values of
+    the 4-bit float with 1 sign, 2 exponent and 1 mantissa bit (code = s e e m), divided by the largest (6)."""
+    mags = np.array([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0], dtype=np.float64) / 6.0
+    return np.concatenate([mags, -mags]).astype(np.float32)

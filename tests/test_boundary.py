@@ -30,7 +30,8 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(L):
     names = declared_functions()
     assert set(names) >= {"nf4_dequantize", "nf4_dequantize_dq", "nf4_dequant_gemv", "nf4_quantize_ref",
-                          "nf4_quantize", "nf4_dequant_gemm", "nf4_dequant_gemm_workspace_bytes", "nf4_last_hip_error", "nf4_status_string"}
+                          "nf4_quantize", "nf4_dequant_gemm", "nf4_dequant_gemm_workspace_bytes", "nf4_dequantize_codebook",
+                          "nf4_dequantize_dq_codebook", "nf4_quantize_ref_codebook", "nf4_last_hip_error", "nf4_status_string"}
     for name in names:
         assert hasattr(L, name), name
 
@@ -124,6 +125,27 @@ def test_quantize_ref_argument_checks(L):
     assert f(P, 5, 64, P, None, None, None, None, None, None) == E_NULL
     assert f(P, 5, 64, P, P, P, None, P, P, None) == E_NULL             # DQ wants all four outputs
     assert f(P + 2, 5, 64, P, P, None, None, None, None, None) == E_ALIGN
+
+
+def test_codebook_entry_points_argument_checks(L):
+    f = L.nf4_dequantize_codebook
+    assert f(P, P, P, 64, -1, P, 0, None) == E_SIZE
+    assert f(P, P, P, 96, 10, P, 0, None) == E_BS
+    assert f(P, P, None, 64, 0, None, 0, None) == OK
+    assert f(P, P, P + 2, 64, 10, P, 0, None) == E_ALIGN             # codebook is read as floats
+    assert f(None, P, P, 64, 10, P, 0, None) == E_NULL
+    g = L.nf4_dequantize_dq_codebook
+    a = [P] * 5
+    for bad in (0, 3, 100, 1 << 17, -256):
+        assert g(*a, bad, P, 64, 10, P, 0, None) == E_SHAPE         # group must be a power of two in [1, 65536]
+    assert g(*a, 64, None, 64, 0, None, 1, None) == OK
+    assert g(P, P, None, P, P, 64, P, 64, 10, P, 0, None) == E_NULL
+    h = L.nf4_quantize_ref_codebook
+    assert h(P, -1, 64, P, 256, P, P, None, None, None, None, None) == E_SIZE
+    assert h(P, 5, 64, P, 100, P, P, P, P, P, P, None) == E_SHAPE
+    assert h(None, 0, 64, None, 256, None, None, None, None, None, None, None) == OK
+    assert h(P, 5, 64, P + 1, 256, P, P, None, None, None, None, None) == E_ALIGN
+    assert h(P, 5, 64, P, 256, P, P, P, None, P, P, None) == E_NULL
 
 
 def test_quantize_argument_checks(L):

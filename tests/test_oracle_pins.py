@@ -412,6 +412,7 @@ def test_e2m1_codebook_is_the_published_value_set():
     t = e2m1_codebook().astype(np.float64) * 6.0
     assert np.allclose(t[:8], [0, 0.5, 1, 1.5, 2, 3, 4, 6], atol=1e-6) and np.allclose(t[8:], -t[:8], atol=1e-6)
     assert np.signbit(e2m1_codebook()[8]) and not np.signbit(e2m1_codebook()[0])      # -0 and +0 are two codes
+    assert np.array_equal(synth.e2m1_codebook().view(np.uint32), e2m1_codebook().view(np.uint32))   # the shared input
 
 
 def test_codebook_functions_with_the_nf4_table_are_the_nf4_functions():
