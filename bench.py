@@ -48,7 +48,7 @@ def parse():
     ap.add_argument("--layers", type=int, default=None, help="override the 80 layers (debugging only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true")
-    ap.add_argument("--extra-legs", default="dq,gemv,quantize,layer",
+    ap.add_argument("--extra-legs", default="dq,gemv,quantize,layer,formats",
                     help="comma list of the extra legs to run: dq, gemv, quantize, layer")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="finish with one plain 256 MiB -> 256 MiB device copy (calibrates rocprofv3 byte counters)")
@@ -171,7 +171,8 @@ def main():
                                                       * layers / 1e3, 4)
     if not args.no_extra:
         legs = {"dq": ("dq_bf16_gemma27b", leg_dq), "gemv": ("gemv_70b_mlp", leg_gemv),
-                "quantize": ("quantize_70b_gate", leg_quantize), "layer": ("layer_replay_qwen3_32b", leg_layer_replay)}
+                "quantize": ("quantize_70b_gate", leg_quantize), "layer": ("layer_replay_qwen3_32b", leg_layer_replay),
+                "formats": ("block_sizes_and_codebooks_8192x28672", leg_formats)}
         result["extra"] = {}
         for key in args.extra_legs.split(","):
             if key:
@@ -237,6 +238,55 @@ def leg_dq(torch, nf4, synth, stream, gen, src):
     return {"elements": elems, "us_per_pass": round(us, 2), "GB/s": round(gbps, 1),
             "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
             "note": "0.98 GB per pass: partly served by the 256 MB last-level cache"}
+
+
+def leg_formats(torch, nf4, synth, stream, gen, src):
+    """The data type as a parameter: one 8192 x 28672 tensor dequantised to FP16 with block sizes 64..4096
+    (FP32 absmax), with an FP4-style codebook read from memory, and with double-quantised scales in second-level
+    groups of 64 and 256.  Bytes per element: 0.5 + 4 / blocksize (or 1 / blocksize + 4 / (blocksize * group)) + 2."""
+    dev = src.device
+    N, K = synth.GEMV_SHAPES[0]
+    n = N * K
+    res = {}
+    w = src[:n]
+    with torch.cuda.stream(stream):
+        gen.manual_seed(8100)
+        w.normal_(0.0, synth.LLAMA33_70B_SIGMA, generator=gen)
+        cb = torch.from_numpy(synth.e2m1_codebook()).to(dev)
+    out = torch.empty(n, dtype=torch.float16, device=dev)
+    # 3 copies of the codes are cycled so that they come from HBM, not from the 256 MB last-level cache
+    for label, blocksize, codebook, group in (("nf4_bs64", 64, None, 0), ("nf4_bs128", 128, None, 0),
+                                              ("nf4_bs256", 256, None, 0), ("nf4_bs1024", 1024, None, 0),
+                                              ("nf4_bs4096", 4096, None, 0), ("e2m1_bs64", 64, cb, 0),
+                                              ("e2m1_bs64_dq_group256", 64, cb, 256),
+                                              ("e2m1_bs128_dq_group64", 128, cb, 64)):
+        copies = []
+        with torch.cuda.stream(stream):
+            for c in range(3):
+                b = nf4.alloc_quantized(n, blocksize, dq=group > 0, device=dev, dq_group=max(group, 1))
+                if c == 0:
+                    nf4.nf4_quantize_ref_codebook(w, n, blocksize, codebook, max(group, 1), b["packed"], b["absmax"],
+                                                  b.get("absmax_q8"), b.get("scale2"), b.get("offset"), b.get("code2"),
+                                                  stream=stream)
+                else:
+                    for k in b:
+                        b[k].copy_(copies[0][k])
+                copies.append(b)
+
+        def run():
+            for b in copies:
+                if group:
+                    nf4.nf4_dequantize_dq_codebook(b["packed"], b["absmax_q8"], b["scale2"], b["offset"], b["code2"],
+                                                   group, codebook, blocksize, n, out, stream=stream)
+                else:
+                    nf4.nf4_dequantize_codebook(b["packed"], b["absmax"], codebook, blocksize, n, out, stream=stream)
+        us = time_on_stream(torch, stream, run, 10) / len(copies)
+        bpe = 0.5 + 2.0 + (1.0 / blocksize + 4.0 / (blocksize * group) if group else 4.0 / blocksize)
+        gbps = n * bpe / (us * 1e-6) / 1e9
+        res[label] = {"us": round(us, 2), "bytes_per_elem": round(bpe, 5), "GB/s": round(gbps, 1),
+                      "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4)}
+        del copies
+    return res
 
 
 GEMM_BATCHES = (1, 4, 16, 32, 64)
@@ -322,9 +372,15 @@ def leg_quantize(torch, nf4, synth, stream, gen, src):
     us = time_on_stream(torch, stream, lambda: nf4.nf4_quantize(w, n, 64, b["packed"], b["absmax"], stream=stream), 20)
     us_ref = time_on_stream(torch, stream,
                             lambda: nf4.nf4_quantize_ref(w, n, 64, b["packed"], b["absmax"], stream=stream), 5)
-    return {"elements": n, "us": round(us, 2), "GB/s": round(bytes_ / (us * 1e-6) / 1e9, 1),
-            "frac_of_hbm_peak": round(bytes_ / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
-            "reference_quantizer_us": round(us_ref, 2)}
+    res = {"elements": n, "us": round(us, 2), "GB/s": round(bytes_ / (us * 1e-6) / 1e9, 1),
+           "frac_of_hbm_peak": round(bytes_ / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+           "reference_quantizer_us": round(us_ref, 2), "other_block_sizes": {}}
+    for bs in (128, 512, 2048):
+        bb = nf4.alloc_quantized(n, bs, device=src.device)
+        t = time_on_stream(torch, stream, lambda: nf4.nf4_quantize(w, n, bs, bb["packed"], bb["absmax"], stream=stream), 10)
+        by = n * (4.0 + 0.5 + 4.0 / bs)
+        res["other_block_sizes"][str(bs)] = {"us": round(t, 2), "GB/s": round(by / (t * 1e-6) / 1e9, 1)}
+    return res
 
 
 def leg_layer_replay(torch, nf4, synth, stream, gen, src):

@@ -1,4 +1,4 @@
-// Tuned NF4 quantiser for gfx950 (blocksize 64): the forward direction of
+// Tuned NF4 quantiser for gfx950 (block sizes 64 to 2048): the forward direction of
 // Sec. II-B, bit-identical to the reference quantiser (and so to the CPU
 // definition), at HBM speed.
 //
@@ -19,10 +19,12 @@
 // costs one table read, one compare and one add.
 //
 // Data movement: one wave per 2048 elements; eight 128-bit loads per lane, each
-// contiguous across the wave; a quantisation block is then spread over the 16
-// lanes of one DPP row (4 elements each), so its absmax is 3 in-lane and 4 DPP
-// max operations and needs no LDS; codes leave as eight 2-byte stores per lane,
-// each instruction writing one full 128-byte line.
+// contiguous across the wave; a block of 64 is then spread over the 16 lanes of
+// one DPP row (4 elements each), so its absmax is 3 in-lane and 4 DPP max
+// operations and needs no LDS; larger blocks add one or two cross-row exchanges
+// (ds_bpermute) and, from 512 on, a maximum over 2, 4 or 8 of the lane's own
+// loads; codes leave as eight 2-byte stores per lane, each instruction writing
+// one full 128-byte line.
 #include <math.h>
 #include <string.h>
 
@@ -126,9 +128,25 @@ __device__ __forceinline__ float div_by_block_scale(float x, float a, float r) {
     return __builtin_fmaf(e2, r, q1);
 }
 
+// Maximum over the lanes that differ in bit 4 (and bit 5) of the lane number: the rows of a wave.
+__device__ __forceinline__ float max_across_rows(float a, int lane, bool all_four) {
+    const float o = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((lane ^ 16) << 2, __builtin_bit_cast(int, a)));
+    a = __builtin_fmaxf(a, o);
+    if (all_four) {
+        const float p = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, __builtin_bit_cast(int, a)));
+        a = __builtin_fmaxf(a, p);
+    }
+    return a;
+}
+
+// LOG2BS = log2(blocksize), 6..11: a block is one DPP row of one load (64), two or four rows of one load
+// (128, 256), or the whole wave over 2, 4 or 8 consecutive loads (512, 1024, 2048).
+template <int LOG2BS>
 __global__ __launch_bounds__(kWave) void quantize_tiles_kernel(const float* __restrict__ src, QuantBins qb,
                                                                uint8_t* __restrict__ packed,
                                                                float* __restrict__ absmax) {
+    constexpr int kLoadsPerBlock = LOG2BS <= 8 ? 1 : (1 << (LOG2BS - 8));
+    constexpr int kBlocksPerTile = kQTileElems >> LOG2BS;
     __shared__ float theta_lds[kBins];
     __shared__ uint32_t base_lds[kBins];
     const int lane = threadIdx.x;
@@ -146,27 +164,56 @@ __global__ __launch_bounds__(kWave) void quantize_tiles_kernel(const float* __re
 #pragma unroll
     for (int j = 0; j < 8; ++j) v[j] = __builtin_nontemporal_load(in + j * kWave + lane);
 
-    uint16_t* out16 = (uint16_t*)(packed + t * (kQTileElems / 2));
-    float* amax_tile = absmax + t * (kQTileElems / 64);
+    // ---- block maxima.  Lane holds elements 256 j + 4 lane .. + 3 of the tile.
+    float a[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        // lane holds elements 256 j + 4 lane .. + 3; block 4 j + lane / 16 is one DPP row
-        float a = __builtin_fmaxf(__builtin_fmaxf(fabsf(v[j][0]), fabsf(v[j][1])),
+        float m = __builtin_fmaxf(__builtin_fmaxf(fabsf(v[j][0]), fabsf(v[j][1])),
                                   __builtin_fmaxf(fabsf(v[j][2]), fabsf(v[j][3])));
-        a = dpp_max<0xB1>(a);      // quad_perm [1,0,3,2]
-        a = dpp_max<0x4E>(a);      // quad_perm [2,3,0,1]
-        a = dpp_max<0x141>(a);     // row_half_mirror
-        a = dpp_max<0x140>(a);     // row_mirror: all 16 lanes hold the block's absmax
-        if ((lane & 15) == 0) amax_tile[4 * j + (lane >> 4)] = a;
-
-        float xn[4];
-        if (a >= 0x1p-64f && a <= 0x1p+64f) {             // same for the 16 lanes of the block
-            const float r0 = __builtin_amdgcn_rcpf(a);
-            const float r = __builtin_fmaf(__builtin_fmaf(-a, r0, 1.0f), r0, r0);
+        m = dpp_max<0xB1>(m);      // quad_perm [1,0,3,2]
+        m = dpp_max<0x4E>(m);      // quad_perm [2,3,0,1]
+        m = dpp_max<0x141>(m);     // row_half_mirror
+        m = dpp_max<0x140>(m);     // row_mirror: all 16 lanes of the row hold the maximum of its 64 elements
+        a[j] = m;
+    }
+    if constexpr (LOG2BS > 8) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) xn[e] = div_by_block_scale(v[j][e], a, r);
+        for (int j0 = 0; j0 < 8; j0 += kLoadsPerBlock) {
+            float m = a[j0];
+#pragma unroll
+            for (int i = 1; i < kLoadsPerBlock; ++i) m = __builtin_fmaxf(m, a[j0 + i]);
+#pragma unroll
+            for (int i = 0; i < kLoadsPerBlock; ++i) a[j0 + i] = m;
+        }
+    }
+    if constexpr (LOG2BS >= 7) {
+#pragma unroll
+        for (int j = 0; j < 8; j += kLoadsPerBlock) {
+            const float m = max_across_rows(a[j], lane, LOG2BS >= 8);
+#pragma unroll
+            for (int i = 0; i < kLoadsPerBlock; ++i) a[j + i] = m;
+        }
+    }
+    float* amax_tile = absmax + t * kBlocksPerTile;
+#pragma unroll
+    for (int j = 0; j < 8; j += kLoadsPerBlock) {
+        // first lane of each block writes its scale; block of element 256 j + 4 lane
+        const int first_lane_mask = LOG2BS >= 8 ? 63 : ((1 << (LOG2BS - 2)) - 1);
+        if ((lane & first_lane_mask) == 0) amax_tile[(256 * j + 4 * lane) >> LOG2BS] = a[j];
+    }
+
+    uint16_t* out16 = (uint16_t*)(packed + t * (kQTileElems / 2));
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const float aj = a[j];
+        float xn[4];
+        if (aj >= 0x1p-64f && aj <= 0x1p+64f) {           // same for all lanes of the block
+            const float r0 = __builtin_amdgcn_rcpf(aj);
+            const float r = __builtin_fmaf(__builtin_fmaf(-aj, r0, 1.0f), r0, r0);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) xn[e] = div_by_block_scale(v[j][e], aj, r);
         } else {
-            const float div = a == 0.0f ? 1.0f : a;       // all-zero block: 0 / 1 = 0 -> code 7
+            const float div = aj == 0.0f ? 1.0f : aj;     // all-zero block: 0 / 1 = 0 -> code 7
 #pragma unroll
             for (int e = 0; e < 4; ++e) xn[e] = v[j][e] / div;   // generic IEEE division
         }
@@ -180,6 +227,14 @@ __global__ __launch_bounds__(kWave) void quantize_tiles_kernel(const float* __re
         const uint32_t two_bytes = (code[0] << 4) | code[1] | (code[2] << 12) | (code[3] << 8);
         __builtin_nontemporal_store((uint16_t)two_bytes, out16 + j * 64 + lane);   // bytes 128 j + 2 lane
     }
+}
+
+template <int LOG2BS>
+static int launch_tiles(const float* src, const QuantBins& qb, int64_t tiles, uint8_t* packed, float* absmax,
+                        hipStream_t s) {
+    hipLaunchKernelGGL(quantize_tiles_kernel<LOG2BS>, dim3((unsigned)tiles), dim3(kWave), 0, s, src, qb, packed,
+                       absmax);
+    return record_hip(hipGetLastError());
 }
 
 // the reference kernel (nf4_quantize_ref.hip) finishes what does not fill a tile
@@ -198,16 +253,26 @@ extern "C" int nf4_quantize(const float* src, int64_t n, int blocksize, uint8_t*
     if (!aligned(src, 16) || !aligned(absmax, 4) || !aligned(packed, 2)) return NF4_ERR_ALIGN;
     hipStream_t s = (hipStream_t)stream;
     const QuantBins* qb = quant_bins();
-    if (blocksize != 64 || qb == nullptr) return launch_quantize_ref_range(src, n, blocksize, nullptr, packed, absmax, s);
+    const int log2_bs = log2_blocksize(blocksize);
+    // a block of 4096 does not fit the 2048-element tile of a wave: the reference kernel does those
+    if (log2_bs > 11 || qb == nullptr) return launch_quantize_ref_range(src, n, blocksize, nullptr, packed, absmax, s);
 
     const int64_t tiles = n / kQTileElems;
     if (tiles > 0x7fffffffLL) return NF4_ERR_SIZE;
     if (tiles > 0) {
-        hipLaunchKernelGGL(quantize_tiles_kernel, dim3((unsigned)tiles), dim3(kWave), 0, s, src, *qb, packed, absmax);
-        const int rc = record_hip(hipGetLastError());
+        int rc = NF4_OK;
+        switch (log2_bs) {
+            case 6: rc = launch_tiles<6>(src, *qb, tiles, packed, absmax, s); break;
+            case 7: rc = launch_tiles<7>(src, *qb, tiles, packed, absmax, s); break;
+            case 8: rc = launch_tiles<8>(src, *qb, tiles, packed, absmax, s); break;
+            case 9: rc = launch_tiles<9>(src, *qb, tiles, packed, absmax, s); break;
+            case 10: rc = launch_tiles<10>(src, *qb, tiles, packed, absmax, s); break;
+            default: rc = launch_tiles<11>(src, *qb, tiles, packed, absmax, s); break;
+        }
         if (rc != NF4_OK) return rc;
     }
-    const int64_t done = tiles * kQTileElems;
+    const int64_t done = tiles * kQTileElems;               // a multiple of every block size up to 2048
     if (done == n) return NF4_OK;
-    return launch_quantize_ref_range(src + done, n - done, 64, nullptr, packed + done / 2, absmax + done / 64, s);
+    return launch_quantize_ref_range(src + done, n - done, blocksize, nullptr, packed + done / 2,
+                                     absmax + (done >> log2_bs), s);
 }

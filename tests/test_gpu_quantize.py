@@ -128,3 +128,20 @@ def test_tuned_equals_reference_on_a_70b_gate_projection():
     torch.cuda.synchronize()
     assert torch.equal(ref["absmax"], tuned["absmax"])
     assert torch.equal(ref["packed"], tuned["packed"])
+
+
+@pytest.mark.parametrize("blocksize", [128, 256, 512, 1024, 2048, 4096])
+@pytest.mark.parametrize("n", [2048 * 37, 2048 * 5 + 4096 + 17, 2048, 100])
+def test_other_block_sizes_match_the_oracle(blocksize, n):
+    """Blocks of 128 to 2048 run in the tuned kernel (cross-row and cross-load maxima), 4096 and ragged ends
+    in the reference kernel; codes and scales are the oracle's either way."""
+    w = synth.gaussian_weights(n, 0.02, seed=blocksize + n % 101, outlier_p=0.002)
+    w[2048:2048 + 64] = 0.0                                  # zeros inside a larger block
+    if n >= 2048 * 5:
+        w[4096:4096 + blocksize] = 0.0                       # an all-zero block
+        w[3 * 2048 - 1] = 7.5                                # the maximum as the last element of a tile
+        w[2 * 2048] = -9.25                                  # ... and as the first, negative
+    p, a = oracle.quantize(w, blocksize)
+    gp, ga = quantize_gpu(w, blocksize)
+    assert np.array_equal(ga.view(np.uint32), a.view(np.uint32))
+    assert np.array_equal(gp, p)

@@ -44,7 +44,7 @@ def test_random_dequantize_cases():
 def test_random_quantize_cases():
     rng = np.random.Generator(np.random.PCG64(2025))
     for case in range(60):
-        bs = int(rng.choice([64, 64, 64, 128, 512, 4096]))
+        bs = int(rng.choice([64, 64, 64, 128, 256, 512, 1024, 2048, 4096]))
         n = int(rng.integers(1, 5 * 2048 + 300))
         w = synth.gaussian_weights(n, float(rng.uniform(1e-4, 3.0)), seed=30_000 + case, outlier_p=0.01)
         if case % 4 == 0:
@@ -57,6 +57,44 @@ def test_random_quantize_cases():
             torch.cuda.synchronize()
             assert np.array_equal(bufs["absmax"].cpu().numpy()[:a.size], a), f"case {case} n={n} bs={bs} {fn.__name__}"
             assert np.array_equal(bufs["packed"].cpu().numpy()[:p.size], p), f"case {case} n={n} bs={bs} {fn.__name__}"
+
+
+def test_random_codebook_cases():
+    """Random codebooks (any order, any magnitude, repeated and zero levels), block sizes and second-level
+    group sizes: quantise with the reference quantiser and dequantise, both against the oracle."""
+    rng = np.random.Generator(np.random.PCG64(2026))
+    for case in range(60):
+        bs = int(rng.choice([64, 128, 256, 1024, 4096]))
+        group = int(rng.choice([1, 2, 32, 256, 2048]))
+        n = int(rng.integers(1, 4 * 2048 + 500))
+        cb = (rng.standard_normal(16) * float(rng.choice([0.3, 1.0, 50.0]))).astype(np.float32)
+        if case % 3 == 0:
+            cb[int(rng.integers(0, 16))] = 0.0
+        if case % 5 == 0:
+            cb[3] = cb[11]                                         # two codes with the same level: the lower wins
+        w = synth.gaussian_weights(n, float(rng.uniform(1e-3, 2.0)), seed=40_000 + case, outlier_p=0.01)
+        p, a = oracle.quantize_codebook(w, cb, blocksize=bs)
+        q8, s2, off, c2 = oracle.dq_encode_group(a, group)
+        bufs = nf4.alloc_quantized(n, bs, dq=True, dq_group=group)
+        dcb = dev(cb)
+        nf4.nf4_quantize_ref_codebook(dev(w), n, bs, dcb, group, bufs["packed"], bufs["absmax"], bufs["absmax_q8"],
+                                      bufs["scale2"], bufs["offset"], bufs["code2"])
+        torch.cuda.synchronize()
+        tag = f"case {case}: n={n} bs={bs} group={group}"
+        assert np.array_equal(bufs["packed"].cpu().numpy()[:p.size], p), tag
+        assert np.array_equal(bufs["absmax"].cpu().numpy()[:a.size], a), tag
+        assert np.array_equal(bufs["absmax_q8"].cpu().numpy()[:q8.size], q8), tag
+        assert np.array_equal(bufs["scale2"].cpu().numpy()[:s2.size], s2), tag
+        assert np.array_equal(bufs["offset"].cpu().numpy(), off), tag
+        bf16 = bool(case & 1)
+        tdt, odt = (torch.bfloat16, oracle.BF16) if bf16 else (torch.float16, oracle.FP16)
+        whole, out = out_buffer(n, tdt)
+        nf4.nf4_dequantize_dq_codebook(bufs["packed"], bufs["absmax_q8"], bufs["scale2"], bufs["offset"], bufs["code2"],
+                                       group, dcb, bs, n, out)
+        torch.cuda.synchronize()
+        want = oracle.dequantize_dq_codebook(p, q8, s2, off, c2, group, cb, n, blocksize=bs, out_dtype=odt)
+        assert mismatches(bits(out), want, bf16) == 0, tag
+        assert guard_intact(whole, n), tag
 
 
 def test_random_gemv_and_gemm_cases():
