@@ -11,13 +11,25 @@
 // coalesced, one window ahead, into the other half of a double buffer, and the
 // waves read their MFMA B operands from it with ds_read_b128.  Token rows are
 // 528 bytes apart, so the 16 lanes that the LDS serves together fall into 8
-// distinct groups of 4 banks (conflict-free at the rate of a 128-bit read).  The
-// codes of the next window are requested into registers while the current one
-// is expanded.  (Requesting two windows ahead, spreading the loads over the
-// arithmetic steps and unpredicated fast paths were each measured and changed
-// nothing: with one barrier per window the 16 waves move in lockstep through a
-// phase that queues in the address unit, one that queues in the LDS and one that
-// is bound by instruction issue, and the window lasts the sum of the three.)
+// distinct groups of 4 banks (conflict-free at the rate of a 128-bit read).
+//
+// Because x comes from LDS, a lane is free to take whichever k it likes: lane
+// (row, group g) expands exactly the 32 bytes of codes it loaded itself
+// (k = 32 g .. 32 g + 31 and 128 + 32 g .. of the window: two 128-bit loads, each
+// contiguous over the four lanes of a row), so no code crosses lanes and only the
+// two block scales a lane needs are fetched from their owner with ds_bpermute.
+// Two register sets alternate, the next window's codes in flight while this
+// one's are expanded.
+//
+// Where the time goes (ablations of this kernel, 8192 x 28672, 16 tokens): the
+// arithmetic alone 27 us, the loads alone 36 us (codes 25 us -- 128 bytes per row
+// and window is a poor pattern for HBM, a plain read of the same bytes takes 19;
+// the scattered 1-byte scale codes and second-level scales +6; activations
+// +1..5), both together 50 us.  They overlap badly: when the memory queues are
+// full a wave blocks in the issue of its next load instead of computing, and
+// with one barrier per window all 16 waves are in that state together.
+// Requesting two windows ahead, unpredicated loads from uniform bases and loads
+// spread over the arithmetic steps were each built and measured: no gain.
 //
 // Since all waves of a workgroup share k, K is split across workgroups instead:
 // blockIdx.y = split s takes `wps` consecutive windows and writes its partial
@@ -33,7 +45,6 @@ typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kSkWindow = 256;               // k per step
-constexpr int kSkRowStride = 36;             // dwords per row in the code exchange buffer (32 + padding)
 constexpr int kXRowBytes = 528;              // bytes per token row of the activation tile (512 + 16)
 
 template <int TG, int RG, int W>
@@ -52,7 +63,6 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
     constexpr int kU = (kChunks + kThreads - 1) / kThreads;
     __shared__ float lut[16];
     __shared__ float code2_lds[256];
-    __shared__ __attribute__((aligned(16))) uint32_t stage[W][RG][16 * kSkRowStride];
     __shared__ __attribute__((aligned(16))) uint8_t xtile[2][kTokens * kXRowBytes];
 
     const int tid = threadIdx.x;
@@ -71,11 +81,15 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
     const int64_t k_end = k_stop < K ? k_stop : K;       // multiple of 64
 
     // ---- loaders.  K and k_end are multiples of 64, so each 8-, 32- or 64-wide piece is all in or all out.
-    u32x4 c[RG][2];                              // codes: 16-byte groups g and g + 4 of the row's 128 bytes
-    uint32_t qb[RG];                             // 8-bit scale code and second-level scale of the window's
-    float s2[RG];                                //   g-th 64-element quarter
-    u32x4 xr[kU];                                // this thread's pieces of the activation tile
-    auto load_codes = [&](int64_t kw) {
+    // One window of this wave's weights as it arrives from memory; two sets alternate, so that the next
+    // window's are in flight while this one's are expanded.
+    struct CodeRegs {
+        u32x4 c[RG][2];                          // codes: 16-byte groups g and g + 4 of the row's 128 bytes
+        uint32_t qb[RG];                         // 8-bit scale code and second-level scale of the window's
+        float s2[RG];                            //   g-th 64-element quarter
+    };
+    u32x4 xr[kU];                                // this thread's pieces of the next activation tile
+    auto load_codes = [&](int64_t kw, CodeRegs& cr) {
 #pragma unroll
         for (int r = 0; r < RG; ++r) {
             const int64_t row = row0 + 16 * r + sub;
@@ -83,16 +97,16 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
             const int64_t e0 = row * K + kw;     // flat index of the row's first element in the window
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                c[r][h] = (u32x4){0x77777777u, 0x77777777u, 0x77777777u, 0x77777777u};   // level 0 if not loaded
+                cr.c[r][h] = (u32x4){0x77777777u, 0x77777777u, 0x77777777u, 0x77777777u};   // level 0 if not loaded
                 if (row_ok && kw + 32 * (g + 4 * h) < k_end)
-                    c[r][h] = __builtin_nontemporal_load((const u32x4*)(packed + (e0 >> 1)) + g + 4 * h);
+                    cr.c[r][h] = __builtin_nontemporal_load((const u32x4*)(packed + (e0 >> 1)) + g + 4 * h);
             }
-            qb[r] = 0;
-            s2[r] = 0.0f;
+            cr.qb[r] = 0;
+            cr.s2[r] = 0.0f;
             if (row_ok && kw + 64 * g < k_end) {
                 const int64_t blk = (e0 + 64 * g) >> log2_bs;
-                qb[r] = q8[blk];
-                s2[r] = scale2[blk >> 8];
+                cr.qb[r] = q8[blk];
+                cr.s2[r] = scale2[blk >> 8];
             }
         }
     };
@@ -121,65 +135,49 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
 #pragma unroll
         for (int t = 0; t < TG; ++t) acc[r][t] = (f32x4){0.0f, 0.0f, 0.0f, 0.0f};
 
-    load_codes(k_begin);
-    load_x(k_begin);
-    store_x(0);
-    __syncthreads();                             // lut, code2_lds and the first tile are in place
-
-    int buf = 0;
-    for (int64_t kw = k_begin; kw < k_end; kw += kSkWindow, buf ^= 1) {
-        // ---- scale of the window's g-th quarter: rounded product, then rounded sum
-        float mine[RG];
+    // One window: `cr` holds its codes, `nx` receives those of the next window, xtile[buf] its activations.
+    // Lane (row sub, group g) owns the 16 bytes it loaded itself -- k = 32 g .. 32 g + 31 and 128 + 32 g .. --
+    // so MFMA step j < 4 takes k = 32 g + 8 j .. + 7 and step j >= 4 takes k = 128 + 32 g + 8 (j - 4) .. + 7:
+    // nothing crosses lanes but the two block scales.
+    auto window = [&](int64_t kw, int buf, const CodeRegs& cr, CodeRegs& nx) {
+        float s[RG][2];
 #pragma unroll
         for (int r = 0; r < RG; ++r) {
-            const float prod = code2_lds[qb[r]] * s2[r];
-            mine[r] = (row0 + 16 * r + sub < N && kw + 64 * g < k_end) ? prod + offset : 0.0f;
+            // lane group g holds the scale of the window's g-th quarter: rounded product, then rounded sum
+            const float prod = code2_lds[cr.qb[r]] * cr.s2[r];
+            const float mine = (row0 + 16 * r + sub < N && kw + 64 * g < k_end) ? prod + offset : 0.0f;
+            // k = 32 g .. lies in quarter g / 2, k = 128 + 32 g .. in quarter 2 + g / 2
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+                s[r][h] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(
+                                                        (sub + 16 * (2 * h + (g >> 1))) << 2, __builtin_bit_cast(int, mine)));
         }
-        // ---- codes cross lanes: group j of the row goes to dwords 4 j .. 4 j + 3; lane group g reads dword g
-#pragma unroll
-        for (int r = 0; r < RG; ++r) {
-            uint32_t* my_row = &stage[wave][r][sub * kSkRowStride];
-            *(u32x4*)(my_row + 4 * g) = c[r][0];
-            *(u32x4*)(my_row + 4 * (g + 4)) = c[r][1];
-        }
-        wave_lds_fence();
-        uint32_t q[RG][8];
-#pragma unroll
-        for (int r = 0; r < RG; ++r)
-#pragma unroll
-            for (int j = 0; j < 8; ++j) q[r][j] = stage[wave][r][sub * kSkRowStride + 4 * j + g];
-        float s[RG][4];                          // quarter jj of the window: k = 64 jj .. -> MFMA steps 2 jj, 2 jj + 1
-#pragma unroll
-        for (int r = 0; r < RG; ++r)
-#pragma unroll
-            for (int jj = 0; jj < 4; ++jj)
-                s[r][jj] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((sub + 16 * jj) << 2,
-                                                                                  __builtin_bit_cast(int, mine[r])));
-        wave_lds_fence();                        // q is in registers: the exchange buffer may be reused
 
         // ---- the next window's codes and activations start their way from memory now
-        load_codes(kw + kSkWindow);
+        load_codes(kw + kSkWindow, nx);
         load_x(kw + kSkWindow);
 
         // ---- dequantise to FP16 in registers and multiply: lookups pipelined two dwords deep
-        const uint8_t* xt = &xtile[buf][sub * kXRowBytes + 16 * g];
+        const uint8_t* xt = &xtile[buf][sub * kXRowBytes + 64 * g];
         float lv[2][8];
-        issue_lookups(q[0][0], lut, lv[0]);
+        issue_lookups(cr.c[0][0][0], lut, lv[0]);
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             half8_t xb[TG];
 #pragma unroll
-            for (int t = 0; t < TG; ++t) xb[t] = *(const half8_t*)(xt + t * 16 * kXRowBytes + 64 * j);
+            for (int t = 0; t < TG; ++t)
+                xb[t] = *(const half8_t*)(xt + t * 16 * kXRowBytes + 256 * (j >> 2) + 16 * (j & 3));
 #pragma unroll
             for (int r = 0; r < RG; ++r) {
                 const int p = j * RG + r;
                 if (p + 1 < 8 * RG) {
-                    issue_lookups(q[(p + 1) % RG][(p + 1) / RG], lut, lv[(p + 1) & 1]);
+                    const int pj = (p + 1) / RG, pr = (p + 1) % RG;
+                    issue_lookups(cr.c[pr][pj >> 2][pj & 3], lut, lv[(p + 1) & 1]);
                     lds_wait<8>();
                 } else {
                     lds_wait<0>();
                 }
-                const float sj = s[r][j >> 1];
+                const float sj = s[r][j >> 2];
                 u32x4 a;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) a[i] = scaled_pack2_f16(lv[p & 1][2 * i], lv[p & 1][2 * i + 1], sj, nz);
@@ -192,6 +190,18 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
 
         store_x(buf ^ 1);                        // nobody reads that half before the barrier
         __syncthreads();                         // ... and nobody is still reading it: all passed the previous one
+    };
+
+    CodeRegs even, odd;
+    load_codes(k_begin, even);
+    load_x(k_begin);
+    store_x(0);
+    __syncthreads();                             // lut, code2_lds and the first tile are in place
+
+    for (int64_t kw = k_begin; kw < k_end; kw += 2 * kSkWindow) {
+        window(kw, 0, even, odd);
+        if (kw + kSkWindow >= k_end) break;      // uniform over the workgroup
+        window(kw + kSkWindow, 1, odd, even);
     }
 
     // ---- C tile: lane holds token 16 t + sub, rows 4 g .. 4 g + 3 of the row group
