@@ -5,19 +5,19 @@
 //
 // The single-launch kernel lets every wave fetch its own activation operands
 // from L2, and that traffic -- every workgroup re-reads all of x -- bounds it.
-// Here the W waves of a workgroup work on the SAME window of 256 k for W
+// Here the W waves of a workgroup work on the SAME window of 256 or 512 k for W
 // different groups of 16 RG rows, so one copy of the window's activations
-// (16 TG tokens x 512 bytes) in LDS serves them all: the workgroup loads it once,
-// coalesced, one window ahead, into the other half of a double buffer, and the
-// waves read their MFMA B operands from it with ds_read_b128.  Token rows are
-// 528 bytes apart, so the 16 lanes that the LDS serves together fall into 8
-// distinct groups of 4 banks (conflict-free at the rate of a 128-bit read).
+// (16 TG tokens x 2 WIN bytes) in LDS serves them all: the workgroup loads it
+// once, coalesced, one window ahead, into the other half of a double buffer, and
+// the waves read their MFMA B operands from it with ds_read_b128.  Token rows are
+// 2 WIN + 16 bytes apart, so the 16 lanes that the LDS serves together fall into
+// 8 distinct groups of 4 banks (conflict-free at the rate of a 128-bit read).
 //
 // Because x comes from LDS, a lane is free to take whichever k it likes: lane
-// (row, group g) expands exactly the 32 bytes of codes it loaded itself
-// (k = 32 g .. 32 g + 31 and 128 + 32 g .. of the window: two 128-bit loads, each
-// contiguous over the four lanes of a row), so no code crosses lanes and only the
-// two block scales a lane needs are fetched from their owner with ds_bpermute.
+// (row, group g) expands exactly the codes it loaded itself (its h-th 128-bit
+// load is k = 128 h + 32 g .. + 31 of the window, each load contiguous over the
+// four lanes of a row), so no code crosses lanes and only the block scales a
+// lane needs are fetched from their owner with ds_bpermute.
 // Two register sets alternate, the next window's codes in flight while this
 // one's are expanded.
 //
@@ -27,9 +27,13 @@
 // the scattered 1-byte scale codes and second-level scales +6; activations
 // +1..5), both together 50 us.  They overlap badly: when the memory queues are
 // full a wave blocks in the issue of its next load instead of computing, and
-// with one barrier per window all 16 waves are in that state together.
-// Requesting two windows ahead, unpredicated loads from uniform bases and loads
-// spread over the arithmetic steps were each built and measured: no gain.
+// with one barrier per window all 16 waves are in that state together.  The
+// arithmetic alone runs at the issue limit of one instruction per 4 cycles and
+// SIMD (4 waves x 8 steps x 32 instructions x 4 cycles = the 4100 cycles a window
+// of it takes).  Requesting two windows ahead, unpredicated loads from uniform
+// bases, loads spread over the arithmetic steps and windows of 512 k instead of
+// 256 were each built and measured: no gain (the 512 form stayed for up to 32
+// tokens: half as many barriers).
 //
 // Since all waves of a workgroup share k, K is split across workgroups instead:
 // blockIdx.y = split s takes `wps` consecutive windows and writes its partial
@@ -44,10 +48,11 @@ namespace nf4 {
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kSkWindow = 256;               // k per step
-constexpr int kXRowBytes = 528;              // bytes per token row of the activation tile (512 + 16)
+// k per step: 512 for up to 32 tokens (256 bytes of codes per row and step: HBM likes that better than 128,
+// and half as many barriers), 256 above that (the activation tiles of 64 tokens would not fit twice in LDS).
+constexpr int window_of(int token_groups) { return token_groups <= 2 ? 512 : 256; }
 
-template <int TG, int RG, int W>
+template <int TG, int RG, int W, int WIN>
 __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* __restrict__ packed,
                                                                 const uint8_t* __restrict__ q8,
                                                                 const float* __restrict__ scale2,
@@ -59,7 +64,10 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
                                                                 _Float16* __restrict__ y) {
     constexpr int kThreads = W * kWave;
     constexpr int kTokens = 16 * TG;
-    constexpr int kChunks = kTokens * 32;        // 16-byte pieces of one activation tile
+    constexpr int kH = WIN / 128;                // 128-bit pieces of codes per lane and row: k = 128 h + 32 g ..
+    constexpr int kXRowBytes = 2 * WIN + 16;     // token row of the activation tile: an odd number of 16-byte units
+    constexpr int kPiecesPerToken = WIN / 8;     // 16-byte pieces of one token's window
+    constexpr int kChunks = kTokens * kPiecesPerToken;
     constexpr int kU = (kChunks + kThreads - 1) / kThreads;
     __shared__ float lut[16];
     __shared__ float code2_lds[256];
@@ -76,17 +84,17 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
     const int sub = lane & 15;                   // row of a tile (A) / token of a group (B, C)
     const int g = lane >> 4;                     // lane group
     const int64_t row0 = ((int64_t)blockIdx.x * W + wave) * (16 * RG);
-    const int64_t k_begin = (int64_t)blockIdx.y * wps * kSkWindow;
-    const int64_t k_stop = k_begin + (int64_t)wps * kSkWindow;
+    const int64_t k_begin = (int64_t)blockIdx.y * wps * WIN;
+    const int64_t k_stop = k_begin + (int64_t)wps * WIN;
     const int64_t k_end = k_stop < K ? k_stop : K;       // multiple of 64
 
     // ---- loaders.  K and k_end are multiples of 64, so each 8-, 32- or 64-wide piece is all in or all out.
     // One window of this wave's weights as it arrives from memory; two sets alternate, so that the next
     // window's are in flight while this one's are expanded.
     struct CodeRegs {
-        u32x4 c[RG][2];                          // codes: 16-byte groups g and g + 4 of the row's 128 bytes
-        uint32_t qb[RG];                         // 8-bit scale code and second-level scale of the window's
-        float s2[RG];                            //   g-th 64-element quarter
+        u32x4 c[RG][kH];                         // codes: 16-byte groups g + 4 h of the row's WIN / 2 bytes
+        uint32_t qb[RG][kH / 2];                 // 8-bit scale code and second-level scale of the window's
+        float s2[RG][kH / 2];                    //   64-element quarters g and (WIN = 512) g + 4
     };
     u32x4 xr[kU];                                // this thread's pieces of the next activation tile
     auto load_codes = [&](int64_t kw, CodeRegs& cr) {
@@ -96,17 +104,20 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
             const bool row_ok = row < N;
             const int64_t e0 = row * K + kw;     // flat index of the row's first element in the window
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
+            for (int h = 0; h < kH; ++h) {
                 cr.c[r][h] = (u32x4){0x77777777u, 0x77777777u, 0x77777777u, 0x77777777u};   // level 0 if not loaded
                 if (row_ok && kw + 32 * (g + 4 * h) < k_end)
                     cr.c[r][h] = __builtin_nontemporal_load((const u32x4*)(packed + (e0 >> 1)) + g + 4 * h);
             }
-            cr.qb[r] = 0;
-            cr.s2[r] = 0.0f;
-            if (row_ok && kw + 64 * g < k_end) {
-                const int64_t blk = (e0 + 64 * g) >> log2_bs;
-                cr.qb[r] = q8[blk];
-                cr.s2[r] = scale2[blk >> 8];
+#pragma unroll
+            for (int m = 0; m < kH / 2; ++m) {
+                cr.qb[r][m] = 0;
+                cr.s2[r][m] = 0.0f;
+                if (row_ok && kw + 64 * (g + 4 * m) < k_end) {
+                    const int64_t blk = (e0 + 64 * (g + 4 * m)) >> log2_bs;
+                    cr.qb[r][m] = q8[blk];
+                    cr.s2[r][m] = scale2[blk >> 8];
+                }
             }
         }
     };
@@ -114,7 +125,7 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
             const int piece = tid + u * kThreads;
-            const int token = piece >> 5, kc = piece & 31;
+            const int token = piece / kPiecesPerToken, kc = piece % kPiecesPerToken;
             xr[u] = (u32x4){0u, 0u, 0u, 0u};
             if (piece < kChunks && token < B && kw + 8 * kc < k_end)
                 xr[u] = *(const u32x4*)(x + (int64_t)token * K + kw + 8 * kc);
@@ -124,7 +135,7 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
             const int piece = tid + u * kThreads;
-            const int token = piece >> 5, kc = piece & 31;
+            const int token = piece / kPiecesPerToken, kc = piece % kPiecesPerToken;
             if (piece < kChunks) *(u32x4*)(&xtile[buf][token * kXRowBytes + kc * 16]) = xr[u];
         }
     };
@@ -136,33 +147,38 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
         for (int t = 0; t < TG; ++t) acc[r][t] = (f32x4){0.0f, 0.0f, 0.0f, 0.0f};
 
     // One window: `cr` holds its codes, `nx` receives those of the next window, xtile[buf] its activations.
-    // Lane (row sub, group g) owns the 16 bytes it loaded itself -- k = 32 g .. 32 g + 31 and 128 + 32 g .. --
-    // so MFMA step j < 4 takes k = 32 g + 8 j .. + 7 and step j >= 4 takes k = 128 + 32 g + 8 (j - 4) .. + 7:
-    // nothing crosses lanes but the two block scales.
+    // Lane (row sub, group g) owns the 16-byte pieces it loaded itself -- piece h is k = 128 h + 32 g .. + 31 --
+    // so MFMA step j takes k = 128 (j / 4) + 32 g + 8 (j % 4) .. + 7: nothing crosses lanes but block scales.
     auto window = [&](int64_t kw, int buf, const CodeRegs& cr, CodeRegs& nx) {
-        float s[RG][2];
+        float s[RG][kH];
 #pragma unroll
         for (int r = 0; r < RG; ++r) {
-            // lane group g holds the scale of the window's g-th quarter: rounded product, then rounded sum
-            const float prod = code2_lds[cr.qb[r]] * cr.s2[r];
-            const float mine = (row0 + 16 * r + sub < N && kw + 64 * g < k_end) ? prod + offset : 0.0f;
-            // k = 32 g .. lies in quarter g / 2, k = 128 + 32 g .. in quarter 2 + g / 2
+            // lane group g holds the scales of quarters g and g + 4: rounded product, then rounded sum
+            float mine[kH / 2];
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
+            for (int m = 0; m < kH / 2; ++m) {
+                const float prod = code2_lds[cr.qb[r][m]] * cr.s2[r][m];
+                mine[m] = (row0 + 16 * r + sub < N && kw + 64 * (g + 4 * m) < k_end) ? prod + offset : 0.0f;
+            }
+            // piece h lies in quarter 2 h + g / 2, held by lane group (2 h + g / 2) % 4 as its entry h / 2
+#pragma unroll
+            for (int h = 0; h < kH; ++h)
                 s[r][h] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(
-                                                        (sub + 16 * (2 * h + (g >> 1))) << 2, __builtin_bit_cast(int, mine)));
+                                                        (sub + 16 * ((2 * h + (g >> 1)) & 3)) << 2,
+                                                        __builtin_bit_cast(int, mine[h >> 1])));
         }
 
         // ---- the next window's codes and activations start their way from memory now
-        load_codes(kw + kSkWindow, nx);
-        load_x(kw + kSkWindow);
+        load_codes(kw + WIN, nx);
+        load_x(kw + WIN);
 
         // ---- dequantise to FP16 in registers and multiply: lookups pipelined two dwords deep
         const uint8_t* xt = &xtile[buf][sub * kXRowBytes + 64 * g];
+        constexpr int kSteps = 4 * kH;
         float lv[2][8];
         issue_lookups(cr.c[0][0][0], lut, lv[0]);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < kSteps; ++j) {
             half8_t xb[TG];
 #pragma unroll
             for (int t = 0; t < TG; ++t)
@@ -170,7 +186,7 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
 #pragma unroll
             for (int r = 0; r < RG; ++r) {
                 const int p = j * RG + r;
-                if (p + 1 < 8 * RG) {
+                if (p + 1 < kSteps * RG) {
                     const int pj = (p + 1) / RG, pr = (p + 1) % RG;
                     issue_lookups(cr.c[pr][pj >> 2][pj & 3], lut, lv[(p + 1) & 1]);
                     lds_wait<8>();
@@ -198,10 +214,10 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
     store_x(0);
     __syncthreads();                             // lut, code2_lds and the first tile are in place
 
-    for (int64_t kw = k_begin; kw < k_end; kw += 2 * kSkWindow) {
+    for (int64_t kw = k_begin; kw < k_end; kw += 2 * WIN) {
         window(kw, 0, even, odd);
-        if (kw + kSkWindow >= k_end) break;      // uniform over the workgroup
-        window(kw + kSkWindow, 1, odd, even);
+        if (kw + WIN >= k_end) break;            // uniform over the workgroup
+        window(kw + WIN, 1, odd, even);
     }
 
     // ---- C tile: lane holds token 16 t + sub, rows 4 g .. 4 g + 3 of the row group
@@ -248,7 +264,8 @@ SplitPlan plan_split(int64_t N, int64_t K, int B) {
     p.waves = 16;
     const int64_t rows_per_group = 16 * p.rg * p.waves;
     p.row_blocks = (N + rows_per_group - 1) / rows_per_group;
-    const int64_t windows = (K + kSkWindow - 1) / kSkWindow;
+    const int win = window_of(p.tg);
+    const int64_t windows = (K + win - 1) / win;
     int64_t S = compute_units() / (p.row_blocks > 0 ? p.row_blocks : 1);
     if (S < 1) S = 1;
     if (S > windows) S = windows;
@@ -261,7 +278,7 @@ template <int TG, int RG, int W>
 static void launch_splitk(const SplitPlan& p, const uint8_t* packed, const uint8_t* q8, const float* scale2,
                           const float* offset, const float* code2, int log2_bs, int64_t N, int64_t K,
                           const _Float16* x, int B, float* partial, _Float16* y, hipStream_t s) {
-    hipLaunchKernelGGL((gemm_splitk_kernel<TG, RG, W>), dim3((unsigned)p.row_blocks, (unsigned)p.splits),
+    hipLaunchKernelGGL((gemm_splitk_kernel<TG, RG, W, window_of(TG)>), dim3((unsigned)p.row_blocks, (unsigned)p.splits),
                        dim3(W * kWave), 0, s, packed, q8, scale2, offset, code2, log2_bs, N, K, x, B, p.wps,
                        p.splits > 1 ? partial : nullptr, y);
 }
