@@ -33,7 +33,11 @@ def test_captured_calls_replay_bit_exactly():
     ym = torch.empty((B, N), dtype=torch.float16, device="cuda")
     qp = torch.empty((n + 1) // 2, dtype=torch.uint8, device="cuda")
     qa = torch.empty((n + 63) // 64, dtype=torch.float32, device="cuda")
-    outputs = [out16, outbf, yv, ym, qp, qa]
+    ys = torch.empty((B, N), dtype=torch.float16, device="cuda")           # split-K GEMM: two kernels per call
+    ws = torch.empty(nf4.nf4_dequant_gemm_workspace_bytes(N, K, B), dtype=torch.uint8, device="cuda")
+    cb = dev(synth.e2m1_codebook())
+    outcb = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    outputs = [out16, outbf, yv, ym, qp, qa, ys, outcb]
 
     def run(stream):
         nf4.nf4_dequantize(d["p"], d["a"], 64, n, out16, stream=stream)
@@ -41,6 +45,9 @@ def test_captured_calls_replay_bit_exactly():
         nf4.nf4_dequant_gemv(d["pm"], d["mq8"], d["ms2"], d["moff"], d["mc2"], 64, N, K, d["x"], 8, yv, stream=stream)
         nf4.nf4_dequant_gemm(d["pm"], d["mq8"], d["ms2"], d["moff"], d["mc2"], 64, N, K, d["x"], B, ym, stream=stream)
         nf4.nf4_quantize(d["w"], n, 64, qp, qa, stream=stream)
+        nf4.nf4_dequant_gemm(d["pm"], d["mq8"], d["ms2"], d["moff"], d["mc2"], 64, N, K, d["x"], B, ys, workspace=ws,
+                             stream=stream)
+        nf4.nf4_dequantize_dq_codebook(d["p"], d["q8"], d["s2"], d["off"], d["c2"], 256, cb, 64, n, outcb, stream=stream)
 
     side = torch.cuda.Stream()
     run(side)                                              # eager reference (also warms up lazy initialisation)
@@ -52,7 +59,7 @@ def test_captured_calls_replay_bit_exactly():
     with torch.cuda.graph(graph, stream=side):
         run(torch.cuda.current_stream())
     for replay in range(4):
-        for t in outputs:                                  # eager work between replays: poison the outputs
+        for t in outputs + [ws]:                           # eager work between replays: poison outputs and workspace
             t.view(torch.uint8).fill_(0xA5)
         torch.cuda.synchronize()
         graph.replay()
