@@ -87,7 +87,9 @@ int nf4_dequantize_dq(const uint8_t* packed, const uint8_t* absmax_q8, const flo
  * FP32 accumulation, W is [N][K] row-major with double-quantised scales as in
  * nf4_dequantize_dq.  x : FP16 [B][K], y : FP16 [B][N], 1 <= B <= 16, K > 0
  * and K % blocksize == 0 (else NF4_ERR_SHAPE).  packed and x must be 16-byte
- * aligned.
+ * aligned.  Up to 6 tokens W stays the FP32 product (vector-ALU FMAs); from 7
+ * tokens on the sum runs on the matrix cores with W as two FP16 terms, i.e. to
+ * 22 significant bits, which needs |W| < 65504.
  */
 int nf4_dequant_gemv(const uint8_t* packed, const uint8_t* absmax_q8, const float* scale2,
                      const float* offset, const float* code2, int blocksize, int64_t N,

@@ -44,7 +44,10 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kRowStride = 36;               // dwords per row in the exchange buffer (32 + padding)
 
-template <int TG, int RG, int kMWaves>
+// TWO_TERM: the weight enters the matrix cores as two FP16 terms (hi + lo, see two_term_pack2_f16), i.e. as the
+// FP32 product level * scale to 22 bits instead of rounded to FP16 -- the GEMV's definition of W, used by
+// nf4_dequant_gemv for more than 8 tokens.
+template <int TG, int RG, int kMWaves, bool TWO_TERM>
 __global__ __launch_bounds__(kMWaves * kWave) void gemm_kernel(const uint8_t* __restrict__ packed,
                                                                const uint8_t* __restrict__ q8,
                                                                const float* __restrict__ scale2,
@@ -141,13 +144,28 @@ __global__ __launch_bounds__(kMWaves * kWave) void gemm_kernel(const uint8_t* __
                     lds_wait<0>();
                 }
                 const float sj = s[j >> 1];
-                u32x4 a;
+                u32x4 a, a_lo;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) a[i] = scaled_pack2_f16(lv[j & 1][2 * i], lv[j & 1][2 * i + 1], sj, nz);
+                for (int i = 0; i < 4; ++i) {
+                    if constexpr (TWO_TERM) {
+                        uint32_t hi, lo;
+                        two_term_pack2_f16(lv[j & 1][2 * i], lv[j & 1][2 * i + 1], sj, nz, hi, lo);
+                        a[i] = hi;
+                        a_lo[i] = lo;
+                    } else {
+                        a[i] = scaled_pack2_f16(lv[j & 1][2 * i], lv[j & 1][2 * i + 1], sj, nz);
+                    }
+                }
                 const half8_t ah = __builtin_bit_cast(half8_t, a);
 #pragma unroll
                 for (int t = 0; t < TG; ++t)
                     acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah, xb[t][j], acc[r][t], 0, 0, 0);
+                if constexpr (TWO_TERM) {
+                    const half8_t al = __builtin_bit_cast(half8_t, a_lo);
+#pragma unroll
+                    for (int t = 0; t < TG; ++t)
+                        acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(al, xb[t][j], acc[r][t], 0, 0, 0);
+                }
             }
             wave_lds_fence();                    // the exchange buffer is overwritten next
         }
@@ -173,13 +191,22 @@ __global__ __launch_bounds__(kMWaves * kWave) void gemm_kernel(const uint8_t* __
     }
 }
 
-template <int TG, int RG, int W>
+template <int TG, int RG, int W, bool TWO_TERM = false>
 static void launch_gemm(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
                         const float* code2, int log2_bs, int64_t N, int64_t K, const _Float16* x, int B,
                         _Float16* y, hipStream_t s) {
     const unsigned groups = (unsigned)((N + 16 * RG - 1) / (16 * RG));
-    hipLaunchKernelGGL((gemm_kernel<TG, RG, W>), dim3(groups), dim3(W * kWave), 0, s, packed, q8, scale2, offset, code2,
+    hipLaunchKernelGGL((gemm_kernel<TG, RG, W, TWO_TERM>), dim3(groups), dim3(W * kWave), 0, s, packed, q8, scale2, offset, code2,
                        log2_bs, N, K, x, B, y);
+}
+
+// y = x W^T with W = level * scale carried to 22 bits (two FP16 terms) on the matrix cores, at most 16 tokens.
+int launch_gemv_mfma(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
+                     const float* code2, int log2_bs, int64_t N, int64_t K, const _Float16* x, int B, _Float16* y,
+                     hipStream_t s) {
+    if (N >= 16384) launch_gemm<1, 2, 8, true>(packed, q8, scale2, offset, code2, log2_bs, N, K, x, B, y, s);
+    else launch_gemm<1, 2, 16, true>(packed, q8, scale2, offset, code2, log2_bs, N, K, x, B, y, s);
+    return record_hip(hipGetLastError());
 }
 
 }  // namespace nf4

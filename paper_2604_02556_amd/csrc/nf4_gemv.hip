@@ -4,8 +4,10 @@
 // handful of tokens that temporary is the dominant traffic, so it is never
 // written here).
 //
-// Not a dense contraction at these batch sizes, so no MFMA: FP32 FMAs and
-// wave64 DPP reductions.  Layout of the work:
+// Up to 6 tokens this is not a dense contraction, so no MFMA: FP32 FMAs and
+// wave64 DPP reductions, the kernel of this file.  From 7 tokens on the entry
+// point hands the same sum to the matrix-core kernel of nf4_gemm.hip with the
+// FP32 weight carried as two FP16 terms.  Layout of the work here:
 //   * one wave (a single-wave workgroup, one-shot grid) owns R consecutive rows
 //     of W over the whole of K, so no partial sums ever leave the wave and the
 //     summation order is fixed (deterministic results);
@@ -248,7 +250,7 @@ static int gemv_tokens(const uint8_t* packed, const uint8_t* q8, const float* sc
     switch (B) {
         // (tokens, code dwords per lane per row, rows per wave): picked by sweeping on MI355X
         NF4_GEMV_CASE(1, 4, 4) NF4_GEMV_CASE(2, 4, 4) NF4_GEMV_CASE(3, 2, 4) NF4_GEMV_CASE(4, 2, 4)
-        NF4_GEMV_CASE(5, 2, 4) NF4_GEMV_CASE(6, 2, 4) NF4_GEMV_CASE(7, 2, 4) NF4_GEMV_CASE(8, 2, 4)
+        NF4_GEMV_CASE(5, 2, 4) NF4_GEMV_CASE(6, 2, 4)
         default: return NF4_ERR_SHAPE;
     }
 #undef NF4_GEMV_CASE
@@ -256,6 +258,12 @@ static int gemv_tokens(const uint8_t* packed, const uint8_t* q8, const float* sc
 }
 
 }  // namespace nf4
+
+namespace nf4 {
+// Measured on MI355X (8192 x 28672): the FMA kernel takes 30 / 65 / ~80 / ~100 us at 1 / 4 / 6 / 8 tokens, the
+// matrix-core kernel 78-88 us whatever the count.
+constexpr int kMfmaMinTokens = 7;
+}
 
 extern "C" int nf4_dequant_gemv(const uint8_t* packed, const uint8_t* absmax_q8, const float* scale2,
                                 const float* offset, const float* code2, int blocksize, int64_t N,
@@ -276,14 +284,12 @@ extern "C" int nf4_dequant_gemv(const uint8_t* packed, const uint8_t* absmax_q8,
         !aligned(code2, 4))
         return NF4_ERR_ALIGN;
 
-    // More than 8 tokens go as two launches of at most 8 each: 16 tokens' worth of
-    // accumulators and activations do not fit the register file at a useful occupancy,
-    // and the path is ALU-bound there, so re-reading the codes costs little.
-    const int first = B > 8 ? (B + 1) / 2 : B;
-    int rc = gemv_tokens(packed, absmax_q8, scale2, offset, code2, log2_bs, N, K, (const _Float16*)x,
-                         first, (_Float16*)y, s);
-    if (rc == NF4_OK && B > first)
-        rc = gemv_tokens(packed, absmax_q8, scale2, offset, code2, log2_bs, N, K,
-                         (const _Float16*)x + (int64_t)first * K, B - first, (_Float16*)y + (int64_t)first * N, s);
-    return rc;
+    // From kMfmaMinTokens tokens on the sum is a dense enough contraction for the matrix cores: the FP32 weight
+    // level * scale enters them as two FP16 terms (22 significant bits, see two_term_pack2_f16), the activations
+    // as they are, accumulation in FP32.  Below that, FMAs on the vector ALU with the weight never narrowed.
+    if (B >= kMfmaMinTokens)
+        return launch_gemv_mfma(packed, absmax_q8, scale2, offset, code2, log2_bs, N, K, (const _Float16*)x, B,
+                                (_Float16*)y, s);
+    return gemv_tokens(packed, absmax_q8, scale2, offset, code2, log2_bs, N, K, (const _Float16*)x, B,
+                       (_Float16*)y, s);
 }

@@ -37,7 +37,7 @@ def within_bar(y, ref):
     return np.all(np.abs(y.astype(np.float64) - ref) <= 1e-2 * np.abs(ref) + 1e-2 * rms)
 
 
-@pytest.mark.parametrize("B", [1, 2, 3, 4, 5, 8, 11, 16])
+@pytest.mark.parametrize("B", [1, 2, 3, 4, 5, 6, 7, 8, 11, 16])
 @pytest.mark.parametrize("N,K", [(37, 256), (64, 2048 + 512), (9, 8192), (130, 64)])
 def test_small_shapes_all_batches(N, K, B):
     case = make_case(N, K, seed=N * 7 + K)
@@ -76,3 +76,37 @@ def test_zero_activations_and_all_ones_weights():
     y = gemv_gpu(ones, N, K, x)
     want = x.astype(np.float64).sum(axis=1, keepdims=True).repeat(N, 1)
     assert np.allclose(y, want, rtol=2e-3, atol=2e-2)
+
+
+def test_matrix_core_path_carries_the_weight_to_22_bits():
+    """From 7 tokens on the weight enters the matrix cores as two FP16 terms.  With unit-vector activations the
+    result is rne_fp16(hi + lo) for hi + lo = W (1 + e), |e| <= 2^-22 (+ 2^-25 absolute): equal to rne_fp16(W)
+    except within that distance of an FP16 rounding boundary, and never more than one FP16 ulp away."""
+    N, K = 64, 1024
+    case = make_case(N, K, seed=15)
+    w = oracle.dequantize_dq(*case, N * K, out_dtype=oracle.FP32).reshape(N, K)
+    ks = [0, 1, 7, 8, 31, 32, 63, 64, 127, 255, 256, 511, 777, 1023]
+    x = np.zeros((len(ks), K), np.float16)
+    for b, k in enumerate(ks):
+        x[b, k] = 1.0
+    y = gemv_gpu(case, N, K, x)
+    want = w[:, ks].T
+    ulp = np.spacing(np.abs(want).astype(np.float16)).astype(np.float64)
+    err = np.abs(y.astype(np.float64) - want.astype(np.float64))
+    assert np.all(err <= 0.5 * ulp + np.abs(want) * 2.0 ** -21 + 2.0 ** -24)
+    exact = np.mean(y.view(np.uint16) == want.astype(np.float16).view(np.uint16))
+    print(f"two-term path: {exact * 100:.2f} % of {y.size} unit-vector outputs equal rne_fp16(W) bit for bit")
+    assert exact > 0.99
+
+
+def test_matrix_core_path_matches_the_fma_path_closely():
+    """The same tokens through both kernels (6 at a time on the vector ALU, 12 at once on the matrix cores)."""
+    N, K = 96, 4096
+    case = make_case(N, K, seed=16)
+    x = synth.activations_fp16(12, K, seed=17)
+    y_mfma = gemv_gpu(case, N, K, x).astype(np.float64)
+    y_fma = np.concatenate([gemv_gpu(case, N, K, x[:6]), gemv_gpu(case, N, K, x[6:])]).astype(np.float64)
+    _, ref = oracle.dequant_gemv(*case, N, K, x.view(np.uint16))
+    scale = np.abs(ref).max()
+    assert np.abs(y_mfma - ref).max() / scale < 1e-3 and np.abs(y_fma - ref).max() / scale < 1e-3
+    assert np.abs(y_mfma - y_fma).max() / scale < 1e-3
