@@ -192,3 +192,52 @@ def test_gemm_70b_mlp_shapes_both_algorithms(N, K):
         rel = np.abs(got - ref).max() / np.abs(ref).max()
         print(f"gemm N={N} K={K} B={B} split={split}: max err / max |y| = {rel:.2e}")
         assert rel < 2e-3
+
+
+@pytest.mark.parametrize("blocksize,group,tuned", [(128, 64, True), (1024, 256, True), (4096, 16, False)])
+def test_formats_on_the_70b_gate_projection(blocksize, group, tuned):
+    """Other block sizes, an E2M1 codebook from memory and other second-level group sizes at full size
+    (8192 x 28672): the tuned NF4 quantiser (where it covers the block size) and the codebook quantiser against
+    the oracle on sampled blocks, then both dequantisers bit for bit on the same blocks."""
+    n = synth.numel(synth.LLAMA33_70B["gate"])
+    nb = n // blocksize
+    w = draw(n, synth.LLAMA33_70B_SIGMA, 7000 + blocksize)
+    rng = np.random.Generator(np.random.PCG64(blocksize))
+    idx = np.unique(np.concatenate([np.arange(4), np.arange(nb - 4, nb), rng.integers(0, nb, 20_000 * 64 // blocksize)]))
+    ti = torch.from_numpy(idx).cuda()
+    src = w.view(-1, blocksize)[ti].cpu().numpy().reshape(-1)
+
+    # NF4 levels, FP32 absmax, this block size
+    bufs = nf4.alloc_quantized(n, blocksize)
+    (nf4.nf4_quantize if tuned else nf4.nf4_quantize_ref)(w, n, blocksize, bufs["packed"], bufs["absmax"])
+    out = torch.empty(n, dtype=torch.float16, device="cuda")
+    nf4.nf4_dequantize(bufs["packed"], bufs["absmax"], blocksize, n, out)
+    torch.cuda.synchronize()
+    pk = bufs["packed"].view(-1, blocksize // 2)[ti].cpu().numpy().reshape(-1)
+    am = bufs["absmax"][ti].cpu().numpy()
+    op, oa = oracle.quantize(src, blocksize)
+    assert np.array_equal(oa, am) and np.array_equal(op, pk)
+    got = bits16(out.view(torch.int16).view(-1, blocksize)[ti]).reshape(-1)
+    assert np.array_equal(got, oracle.dequantize(pk, am, src.size, blocksize=blocksize))
+
+    # E2M1 codebook, double-quantised scales with this group size, BF16 out
+    cb = synth.e2m1_codebook()
+    dcb = torch.from_numpy(cb).cuda()
+    b2 = nf4.alloc_quantized(n, blocksize, dq=True, dq_group=group)
+    nf4.nf4_quantize_ref_codebook(w, n, blocksize, dcb, group, b2["packed"], b2["absmax"], b2["absmax_q8"], b2["scale2"],
+                                  b2["offset"], b2["code2"])
+    outb = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    nf4.nf4_dequantize_dq_codebook(b2["packed"], b2["absmax_q8"], b2["scale2"], b2["offset"], b2["code2"], group, dcb,
+                                   blocksize, n, outb)
+    torch.cuda.synchronize()
+    pk2 = b2["packed"].view(-1, blocksize // 2)[ti].cpu().numpy().reshape(-1)
+    op2, oa2 = oracle.quantize_codebook(src, cb, blocksize)
+    assert np.array_equal(oa2, b2["absmax"][ti].cpu().numpy()) and np.array_equal(op2, pk2)
+    # the second level over the WHOLE absmax array (the offset is a global mean), then the sampled blocks' scales
+    q8, s2, off, c2 = oracle.dq_encode_group(b2["absmax"].cpu().numpy(), group)
+    assert np.array_equal(q8, b2["absmax_q8"].cpu().numpy()) and np.array_equal(s2, b2["scale2"].cpu().numpy())
+    assert np.array_equal(off.view(np.uint32), b2["offset"].cpu().numpy().view(np.uint32))
+    dec = (c2[q8[idx]] * s2[idx // group]).astype(np.float32) + off[0]
+    want = oracle.dequantize_codebook(pk2, dec, cb, src.size, blocksize=blocksize, out_dtype=oracle.BF16)
+    gotb = bits16(outb.view(torch.int16).view(-1, blocksize)[ti]).reshape(-1)
+    assert np.array_equal(gotb, want)
