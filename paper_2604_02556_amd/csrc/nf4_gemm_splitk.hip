@@ -14,10 +14,12 @@
 // 8 distinct groups of 4 banks (conflict-free at the rate of a 128-bit read).
 //
 // Because x comes from LDS, a lane is free to take whichever k it likes: lane
-// (row, group g) expands exactly the codes it loaded itself (its h-th 128-bit
-// load is k = 128 h + 32 g .. + 31 of the window, each load contiguous over the
-// four lanes of a row), so no code crosses lanes and only the block scales a
-// lane needs are fetched from their owner with ds_bpermute.
+// (row, group g) expands k = 128 h + 32 g .. + 31 of the window as its piece h,
+// i.e. whole 16-byte pieces as they lie in memory.  The loads use another lane
+// numbering than the arithmetic (row = lane / 4, piece = lane % 4 + 4 h, so
+// that a quad of lanes reads 64 contiguous bytes); the pieces change lanes
+// through a per-wave LDS buffer, one 128-bit write and read each, and the block
+// scales come from the lane that loaded them with ds_bpermute.
 // Two register sets alternate, the next window's codes in flight while this
 // one's are expanded.
 //
@@ -68,10 +70,12 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
     constexpr int kXRowBytes = 2 * WIN + 16;     // token row of the activation tile: an odd number of 16-byte units
     constexpr int kPiecesPerToken = WIN / 8;     // 16-byte pieces of one token's window
     constexpr int kChunks = kTokens * kPiecesPerToken;
+    constexpr int kTurnRow = 80;                 // bytes per row in the transpose buffer (64 + 16: conflict-free)
     constexpr int kU = (kChunks + kThreads - 1) / kThreads;
     __shared__ float lut[16];
     __shared__ float code2_lds[256];
     __shared__ __attribute__((aligned(16))) uint8_t xtile[2][kTokens * kXRowBytes];
+    __shared__ __attribute__((aligned(16))) uint8_t turn[W][RG][kH][16 * kTurnRow];   // lane transpose of the codes
 
     const int tid = threadIdx.x;
     if (tid < 16) lut[tid] = __uint_as_float(level_literal(tid));
@@ -83,6 +87,12 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int sub = lane & 15;                   // row of a tile (A) / token of a group (B, C)
     const int g = lane >> 4;                     // lane group
+    // Loads use another numbering of the lanes than the arithmetic: lane l fetches for row l / 4 its piece l % 4,
+    // so that the four lanes of a quad read 64 contiguous bytes.  The address unit of a CU takes about 16 cycles for
+    // a 128-bit load whose quads are contiguous and about 64 (one lane per cycle) when neighbouring lanes are in
+    // different rows, as they are in the MFMA numbering (row = l % 16) -- measured with cache-resident data.
+    const int lrow = lane >> 2;                  // load numbering: row of the tile
+    const int lpc = lane & 3;                    //   and 16-byte piece (codes) / 64-element quarter (scales)
     const int64_t row0 = ((int64_t)blockIdx.x * W + wave) * (16 * RG);
     const int64_t k_begin = (int64_t)blockIdx.y * wps * WIN;
     const int64_t k_stop = k_begin + (int64_t)wps * WIN;
@@ -92,29 +102,29 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
     // One window of this wave's weights as it arrives from memory; two sets alternate, so that the next
     // window's are in flight while this one's are expanded.
     struct CodeRegs {
-        u32x4 c[RG][kH];                         // codes: 16-byte groups g + 4 h of the row's WIN / 2 bytes
+        u32x4 c[RG][kH];                         // codes of row lrow: 16-byte groups lpc + 4 h of its WIN / 2 bytes
         uint32_t qb[RG][kH / 2];                 // 8-bit scale code and second-level scale of the window's
-        float s2[RG][kH / 2];                    //   64-element quarters g and (WIN = 512) g + 4
+        float s2[RG][kH / 2];                    //   64-element quarters lpc and (WIN = 512) lpc + 4
     };
     u32x4 xr[kU];                                // this thread's pieces of the next activation tile
     auto load_codes = [&](int64_t kw, CodeRegs& cr) {
 #pragma unroll
         for (int r = 0; r < RG; ++r) {
-            const int64_t row = row0 + 16 * r + sub;
+            const int64_t row = row0 + 16 * r + lrow;
             const bool row_ok = row < N;
             const int64_t e0 = row * K + kw;     // flat index of the row's first element in the window
 #pragma unroll
             for (int h = 0; h < kH; ++h) {
                 cr.c[r][h] = (u32x4){0x77777777u, 0x77777777u, 0x77777777u, 0x77777777u};   // level 0 if not loaded
-                if (row_ok && kw + 32 * (g + 4 * h) < k_end)
-                    cr.c[r][h] = __builtin_nontemporal_load((const u32x4*)(packed + (e0 >> 1)) + g + 4 * h);
+                if (row_ok && kw + 32 * (lpc + 4 * h) < k_end)
+                    cr.c[r][h] = __builtin_nontemporal_load((const u32x4*)(packed + (e0 >> 1)) + lpc + 4 * h);
             }
 #pragma unroll
             for (int m = 0; m < kH / 2; ++m) {
                 cr.qb[r][m] = 0;
                 cr.s2[r][m] = 0.0f;
-                if (row_ok && kw + 64 * (g + 4 * m) < k_end) {
-                    const int64_t blk = (e0 + 64 * (g + 4 * m)) >> log2_bs;
+                if (row_ok && kw + 64 * (lpc + 4 * m) < k_end) {
+                    const int64_t blk = (e0 + 64 * (lpc + 4 * m)) >> log2_bs;
                     cr.qb[r][m] = q8[blk];
                     cr.s2[r][m] = scale2[blk >> 8];
                 }
@@ -147,26 +157,36 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
         for (int t = 0; t < TG; ++t) acc[r][t] = (f32x4){0.0f, 0.0f, 0.0f, 0.0f};
 
     // One window: `cr` holds its codes, `nx` receives those of the next window, xtile[buf] its activations.
-    // Lane (row sub, group g) owns the 16-byte pieces it loaded itself -- piece h is k = 128 h + 32 g .. + 31 --
-    // so MFMA step j takes k = 128 (j / 4) + 32 g + 8 (j % 4) .. + 7: nothing crosses lanes but block scales.
+    // For the arithmetic lane (row sub, group g) takes piece g + 4 h of its row, k = 128 h + 32 g .. + 31, so MFMA
+    // step j takes k = 128 (j / 4) + 32 g + 8 (j % 4) .. + 7.  The pieces change lanes (4 row + piece -> row +
+    // 16 piece) through the wave's own LDS buffer.
     auto window = [&](int64_t kw, int buf, const CodeRegs& cr, CodeRegs& nx) {
         float s[RG][kH];
+        u32x4 c[RG][kH];
 #pragma unroll
         for (int r = 0; r < RG; ++r) {
-            // lane group g holds the scales of quarters g and g + 4: rounded product, then rounded sum
+#pragma unroll
+            for (int h = 0; h < kH; ++h) *(u32x4*)&turn[wave][r][h][lrow * kTurnRow + 16 * lpc] = cr.c[r][h];
+            // the loading lane holds the scales of quarters lpc and lpc + 4 of row lrow: rounded product, rounded sum
             float mine[kH / 2];
 #pragma unroll
             for (int m = 0; m < kH / 2; ++m) {
                 const float prod = code2_lds[cr.qb[r][m]] * cr.s2[r][m];
-                mine[m] = (row0 + 16 * r + sub < N && kw + 64 * (g + 4 * m) < k_end) ? prod + offset : 0.0f;
+                mine[m] = (row0 + 16 * r + lrow < N && kw + 64 * (lpc + 4 * m) < k_end) ? prod + offset : 0.0f;
             }
-            // piece h lies in quarter 2 h + g / 2, held by lane group (2 h + g / 2) % 4 as its entry h / 2
+            // piece h of the arithmetic lane lies in quarter 2 h + g / 2 of row sub: lane 4 sub + quarter % 4, entry h / 2
 #pragma unroll
             for (int h = 0; h < kH; ++h)
                 s[r][h] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(
-                                                        (sub + 16 * ((2 * h + (g >> 1)) & 3)) << 2,
+                                                        (4 * sub + ((2 * h + (g >> 1)) & 3)) << 2,
                                                         __builtin_bit_cast(int, mine[h >> 1])));
         }
+        wave_lds_fence();
+#pragma unroll
+        for (int r = 0; r < RG; ++r)
+#pragma unroll
+            for (int h = 0; h < kH; ++h) c[r][h] = *(const u32x4*)&turn[wave][r][h][sub * kTurnRow + 16 * g];
+        wave_lds_fence();                        // c is in registers: cr and the buffer may be rewritten
 
         // ---- the next window's codes and activations start their way from memory now
         load_codes(kw + WIN, nx);
@@ -176,7 +196,7 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
         const uint8_t* xt = &xtile[buf][sub * kXRowBytes + 64 * g];
         constexpr int kSteps = 4 * kH;
         float lv[2][8];
-        issue_lookups(cr.c[0][0][0], lut, lv[0]);
+        issue_lookups(c[0][0][0], lut, lv[0]);
 #pragma unroll
         for (int j = 0; j < kSteps; ++j) {
             half8_t xb[TG];
@@ -188,7 +208,7 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
                 const int p = j * RG + r;
                 if (p + 1 < kSteps * RG) {
                     const int pj = (p + 1) / RG, pr = (p + 1) % RG;
-                    issue_lookups(cr.c[pr][pj >> 2][pj & 3], lut, lv[(p + 1) & 1]);
+                    issue_lookups(c[pr][pj >> 2][pj & 3], lut, lv[(p + 1) & 1]);
                     lds_wait<8>();
                 } else {
                     lds_wait<0>();
