@@ -294,15 +294,16 @@ GEMM_BATCHES = (1, 4, 16, 32, 64)
 
 
 def leg_gemv(torch, nf4, synth, stream, gen, src):
-    """y = x W^T on the 70B MLP shapes, double-quantised W, batch 1/4/16; 4 distinct W copies are cycled
-    so that the 112 MiB of codes come from HBM rather than the last-level cache."""
+    """y = x W^T on the 70B MLP shapes, double-quantised W, batch 1/4/16; 8 distinct W copies (0.97 GB) are
+    cycled so that the 112 MiB of codes come from HBM rather than the 256 MB last-level cache (with 4 copies
+    the kernels measured about 10 % faster than they are on cold data)."""
     dev = src.device
     res = {}
     for (N, K) in synth.GEMV_SHAPES:
         n = N * K
         copies = []
         with torch.cuda.stream(stream):
-            for c in range(4):
+            for c in range(8):
                 gen.manual_seed(5000 + c + N)
                 w = src[:n]
                 w.normal_(0.0, synth.LLAMA33_70B_SIGMA, generator=gen)
