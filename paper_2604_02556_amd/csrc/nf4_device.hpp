@@ -118,6 +118,36 @@ __device__ __forceinline__ void issue_lookups(uint32_t q, const float* lut, floa
     }
 }
 
+// The same eight levels from a table indexed by whole code bytes: entry [byte][replica] holds the pair
+// (level[byte >> 4], level[byte & 15]), 32 replicas of 8 bytes per byte value (64 KiB).  Lane l reads replica
+// l % 32, so every lane of a half-wave owns its own pair of LDS banks whatever the codes are, the address is a
+// single byte permute (byte k of q into bits 15:8 above the lane's offset) and one 64-bit read brings two levels:
+// 8 instructions per dword of codes instead of 18.  The table must start at LDS address 0 (the only __shared__
+// object of the kernel, or the first bytes of it) so that the permuted value is the address itself.
+constexpr int kPairReplicas = 32;
+constexpr int kPairTableBytes = 256 * kPairReplicas * 8;
+__device__ __forceinline__ uint32_t pair_lane_offset(int lane) { return (uint32_t)(lane & (kPairReplicas - 1)) * 8u; }
+
+// Fill the table from the 16 levels in `lut` (LDS, already visible to the caller's threads).
+__device__ __forceinline__ void fill_pair_table(float2_t* table, const float* lut, int tid, int threads) {
+    for (int i = tid; i < 256 * kPairReplicas; i += threads) {
+        const int byte = i / kPairReplicas;
+        table[i] = (float2_t){lut[byte >> 4], lut[byte & 15]};
+    }
+}
+
+__device__ __forceinline__ void issue_pair_lookups(uint32_t q, const uint8_t* table, uint32_t lane_off,
+                                                   float (&lv)[8]) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        // result bytes: [0] = lane_off, [1] = byte k of q, [2] = [3] = 0
+        const uint32_t a = __builtin_amdgcn_perm(q, lane_off, 0x0c0c0000u | ((4u + k) << 8));
+        const float2_t pr = *(const float2_t*)(table + a);
+        lv[2 * k] = pr[0];                                         // high nibble = even element
+        lv[2 * k + 1] = pr[1];
+    }
+}
+
 // Wait until at most `left` LDS operations of this wave are outstanding, and keep
 // the instruction scheduler from moving anything across.  The kernel is bound by
 // instruction issue, and a wave spends an issue slot on every s_waitcnt: one wait

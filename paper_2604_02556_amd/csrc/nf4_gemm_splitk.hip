@@ -72,14 +72,24 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
     constexpr int kChunks = kTokens * kPiecesPerToken;
     constexpr int kTurnRow = 80;                 // bytes per row in the transpose buffer (64 + 16: conflict-free)
     constexpr int kU = (kChunks + kThreads - 1) / kThreads;
-    __shared__ float lut[16];
-    __shared__ float code2_lds[256];
-    __shared__ __attribute__((aligned(16))) uint8_t xtile[2][kTokens * kXRowBytes];
-    __shared__ __attribute__((aligned(16))) uint8_t turn[W][RG][kH][16 * kTurnRow];   // lane transpose of the codes
+    constexpr int kXTileBytes = kTokens * kXRowBytes;
+    constexpr int kTurnBytes = 16 * kTurnRow;    // one 16-byte piece of each of 16 rows
+    // One LDS object, so that the level-pair table sits at address 0 (see issue_pair_lookups):
+    // table | two activation tiles | per wave and row group one lane-transpose buffer | code2 | levels
+    constexpr int kOffX = kPairTableBytes, kOffTurn = kOffX + 2 * kXTileBytes;
+    constexpr int kOffCode2 = kOffTurn + W * RG * kTurnBytes, kOffLut = kOffCode2 + 1024;
+    __shared__ __attribute__((aligned(16))) uint8_t smem[kOffLut + 64];
+    static_assert(sizeof(smem) <= 160 * 1024, "LDS of one compute unit");
+    const uint8_t* table = smem;
+    uint8_t* xtile0 = smem + kOffX;
+    float* code2_lds = (float*)(smem + kOffCode2);
+    float* lut = (float*)(smem + kOffLut);
 
     const int tid = threadIdx.x;
     if (tid < 16) lut[tid] = __uint_as_float(level_literal(tid));
     for (int i = tid; i < 256; i += kThreads) code2_lds[i] = code2[i];
+    __syncthreads();
+    fill_pair_table((float2_t*)smem, lut, tid, kThreads);    // visible after the barrier that follows the first tile
     const float offset = offset_p[0];
     const float nz = opaque_neg_zero();
 
@@ -93,6 +103,8 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
     // different rows, as they are in the MFMA numbering (row = l % 16) -- measured with cache-resident data.
     const int lrow = lane >> 2;                  // load numbering: row of the tile
     const int lpc = lane & 3;                    //   and 16-byte piece (codes) / 64-element quarter (scales)
+    const uint32_t lane_off = pair_lane_offset(lane);
+    uint8_t* turn = smem + kOffTurn + wave * (RG * kTurnBytes);   // this wave's transpose buffers
     const int64_t row0 = ((int64_t)blockIdx.x * W + wave) * (16 * RG);
     const int64_t k_begin = (int64_t)blockIdx.y * wps * WIN;
     const int64_t k_stop = k_begin + (int64_t)wps * WIN;
@@ -146,7 +158,7 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
         for (int u = 0; u < kU; ++u) {
             const int piece = tid + u * kThreads;
             const int token = piece / kPiecesPerToken, kc = piece % kPiecesPerToken;
-            if (piece < kChunks) *(u32x4*)(&xtile[buf][token * kXRowBytes + kc * 16]) = xr[u];
+            if (piece < kChunks) *(u32x4*)(xtile0 + buf * kXTileBytes + token * kXRowBytes + kc * 16) = xr[u];
         }
     };
 
@@ -165,8 +177,6 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
         u32x4 c[RG][kH];
 #pragma unroll
         for (int r = 0; r < RG; ++r) {
-#pragma unroll
-            for (int h = 0; h < kH; ++h) *(u32x4*)&turn[wave][r][h][lrow * kTurnRow + 16 * lpc] = cr.c[r][h];
             // the loading lane holds the scales of quarters lpc and lpc + 4 of row lrow: rounded product, rounded sum
             float mine[kH / 2];
 #pragma unroll
@@ -181,22 +191,26 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
                                                         (4 * sub + ((2 * h + (g >> 1)) & 3)) << 2,
                                                         __builtin_bit_cast(int, mine[h >> 1])));
         }
-        wave_lds_fence();
+        // the pieces change lanes one h at a time through the wave's buffer (one per row group)
 #pragma unroll
-        for (int r = 0; r < RG; ++r)
+        for (int h = 0; h < kH; ++h) {
 #pragma unroll
-            for (int h = 0; h < kH; ++h) c[r][h] = *(const u32x4*)&turn[wave][r][h][sub * kTurnRow + 16 * g];
-        wave_lds_fence();                        // c is in registers: cr and the buffer may be rewritten
+            for (int r = 0; r < RG; ++r) *(u32x4*)(turn + r * kTurnBytes + lrow * kTurnRow + 16 * lpc) = cr.c[r][h];
+            wave_lds_fence();
+#pragma unroll
+            for (int r = 0; r < RG; ++r) c[r][h] = *(const u32x4*)(turn + r * kTurnBytes + sub * kTurnRow + 16 * g);
+            wave_lds_fence();                    // read before the next h overwrites the buffer
+        }
 
         // ---- the next window's codes and activations start their way from memory now
         load_codes(kw + WIN, nx);
         load_x(kw + WIN);
 
         // ---- dequantise to FP16 in registers and multiply: lookups pipelined two dwords deep
-        const uint8_t* xt = &xtile[buf][sub * kXRowBytes + 64 * g];
+        const uint8_t* xt = xtile0 + buf * kXTileBytes + sub * kXRowBytes + 64 * g;
         constexpr int kSteps = 4 * kH;
         float lv[2][8];
-        issue_lookups(c[0][0][0], lut, lv[0]);
+        issue_pair_lookups(c[0][0][0], table, lane_off, lv[0]);
 #pragma unroll
         for (int j = 0; j < kSteps; ++j) {
             half8_t xb[TG];
@@ -208,8 +222,8 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
                 const int p = j * RG + r;
                 if (p + 1 < kSteps * RG) {
                     const int pj = (p + 1) / RG, pr = (p + 1) % RG;
-                    issue_lookups(c[pr][pj >> 2][pj & 3], lut, lv[(p + 1) & 1]);
-                    lds_wait<8>();
+                    issue_pair_lookups(c[pr][pj >> 2][pj & 3], table, lane_off, lv[(p + 1) & 1]);
+                    lds_wait<4>();
                 } else {
                     lds_wait<0>();
                 }
