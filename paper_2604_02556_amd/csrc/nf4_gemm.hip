@@ -47,7 +47,9 @@ constexpr int kRowStride = 36;               // dwords per row in the exchange b
 // TWO_TERM: the weight enters the matrix cores as two FP16 terms (hi + lo, see two_term_pack2_f16), i.e. as the
 // FP32 product level * scale to 22 bits instead of rounded to FP16 -- the GEMV's definition of W, used by
 // nf4_dequant_gemv for more than 8 tokens.
-template <int TG, int RG, int kMWaves, bool TWO_TERM>
+// PAIR: levels come from the byte-indexed pair table (issue_pair_lookups) instead of the 16-entry table: fewer
+// instructions, 64 KiB more LDS (the final reduction buffer shares that space).
+template <int TG, int RG, int kMWaves, bool TWO_TERM, bool PAIR>
 __global__ __launch_bounds__(kMWaves * kWave) void gemm_kernel(const uint8_t* __restrict__ packed,
                                                                const uint8_t* __restrict__ q8,
                                                                const float* __restrict__ scale2,
@@ -58,15 +60,25 @@ __global__ __launch_bounds__(kMWaves * kWave) void gemm_kernel(const uint8_t* __
                                                                _Float16* __restrict__ y) {
     constexpr int kMThreads = kMWaves * kWave;
     constexpr int kTiles = RG * TG;              // 16 x 16 output tiles per wave
-    __shared__ float lut[16];
-    __shared__ float code2_lds[256];
-    __shared__ __attribute__((aligned(16))) uint32_t stage[kMWaves][16 * kRowStride];
-    __shared__ float red[kMWaves][kTiles * 4][kWave];
+    // One LDS object: [pair table or nothing | reduction buffer over the same bytes] | exchange rows | code2 | levels
+    constexpr int kRedBytes = kMWaves * kTiles * 4 * kWave * 4;
+    constexpr int kHeadBytes = PAIR ? (kRedBytes > kPairTableBytes ? kRedBytes : kPairTableBytes) : kRedBytes;
+    constexpr int kStageBytes = 16 * kRowStride * 4;
+    constexpr int kOffStage = kHeadBytes, kOffCode2 = kOffStage + kMWaves * kStageBytes, kOffLut = kOffCode2 + 1024;
+    __shared__ __attribute__((aligned(16))) uint8_t smem[kOffLut + 64];
+    static_assert(sizeof(smem) <= 160 * 1024, "LDS of one compute unit");
+    float* lut = (float*)(smem + kOffLut);
+    float* code2_lds = (float*)(smem + kOffCode2);
+    float (*red)[kTiles * 4][kWave] = (float (*)[kTiles * 4][kWave])smem;
 
     const int tid = threadIdx.x;
     if (tid < 16) lut[tid] = __uint_as_float(level_literal(tid));
     for (int i = tid; i < 256; i += kMThreads) code2_lds[i] = code2[i];
     __syncthreads();
+    if constexpr (PAIR) {
+        fill_pair_table((float2_t*)smem, lut, tid, kMThreads);
+        __syncthreads();
+    }
     const float offset = offset_p[0];
     const float nz = opaque_neg_zero();
 
@@ -75,7 +87,13 @@ __global__ __launch_bounds__(kMWaves * kWave) void gemm_kernel(const uint8_t* __
     const int sub = lane & 15;                   // row of a tile (A) / token of a group (B, C)
     const int g = lane >> 4;                     // lane group
     const int64_t row0 = (int64_t)blockIdx.x * (16 * RG);
-    uint32_t* my_row = &stage[wave][sub * kRowStride];
+    uint32_t* my_row = (uint32_t*)(smem + kOffStage + wave * kStageBytes) + sub * kRowStride;
+    const uint32_t lane_off = pair_lane_offset(lane);
+    auto lookups = [&](uint32_t q, float (&lv)[8]) {
+        if constexpr (PAIR) issue_pair_lookups(q, smem, lane_off, lv);
+        else issue_lookups(q, lut, lv);
+    };
+    constexpr int kPerDword = PAIR ? 4 : 8;      // LDS reads per dword of codes
 
     f32x4 acc[RG][TG];
 #pragma unroll
@@ -134,12 +152,12 @@ __global__ __launch_bounds__(kMWaves * kWave) void gemm_kernel(const uint8_t* __
 
             // ---- dequantise to FP16 in registers and multiply: lookups pipelined two dwords deep
             float lv[2][8];
-            issue_lookups(q[0], lut, lv[0]);
+            lookups(q[0], lv[0]);
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 if (j + 1 < 8) {
-                    issue_lookups(q[j + 1], lut, lv[(j + 1) & 1]);
-                    lds_wait<8>();
+                    lookups(q[j + 1], lv[(j + 1) & 1]);
+                    lds_wait<kPerDword>();
                 } else {
                     lds_wait<0>();
                 }
@@ -171,6 +189,7 @@ __global__ __launch_bounds__(kMWaves * kWave) void gemm_kernel(const uint8_t* __
         }
     }
 
+    if constexpr (PAIR) __syncthreads();         // the reduction buffer overwrites the table: every wave is done with it
 #pragma unroll
     for (int r = 0; r < RG; ++r)
 #pragma unroll
@@ -191,12 +210,12 @@ __global__ __launch_bounds__(kMWaves * kWave) void gemm_kernel(const uint8_t* __
     }
 }
 
-template <int TG, int RG, int W, bool TWO_TERM = false>
+template <int TG, int RG, int W, bool TWO_TERM = false, bool PAIR = false>
 static void launch_gemm(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
                         const float* code2, int log2_bs, int64_t N, int64_t K, const _Float16* x, int B,
                         _Float16* y, hipStream_t s) {
     const unsigned groups = (unsigned)((N + 16 * RG - 1) / (16 * RG));
-    hipLaunchKernelGGL((gemm_kernel<TG, RG, W, TWO_TERM>), dim3(groups), dim3(W * kWave), 0, s, packed, q8, scale2, offset, code2,
+    hipLaunchKernelGGL((gemm_kernel<TG, RG, W, TWO_TERM, PAIR>), dim3(groups), dim3(W * kWave), 0, s, packed, q8, scale2, offset, code2,
                        log2_bs, N, K, x, B, y);
 }
 
@@ -204,8 +223,10 @@ static void launch_gemm(const uint8_t* packed, const uint8_t* q8, const float* s
 int launch_gemv_mfma(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
                      const float* code2, int log2_bs, int64_t N, int64_t K, const _Float16* x, int B, _Float16* y,
                      hipStream_t s) {
+    // the pair table pays where its 64 KiB of LDS do not cost a resident workgroup (measured: 72 -> 66 us on
+    // 8192 x 28672; the 8-wave form for tall matrices goes from 79 to 98 us with it)
     if (N >= 16384) launch_gemm<1, 2, 8, true>(packed, q8, scale2, offset, code2, log2_bs, N, K, x, B, y, s);
-    else launch_gemm<1, 2, 16, true>(packed, q8, scale2, offset, code2, log2_bs, N, K, x, B, y, s);
+    else launch_gemm<1, 2, 16, true, true>(packed, q8, scale2, offset, code2, log2_bs, N, K, x, B, y, s);
     return record_hip(hipGetLastError());
 }
 
@@ -250,7 +271,11 @@ extern "C" int nf4_dequant_gemm(const uint8_t* packed, const uint8_t* absmax_q8,
 #define NF4_GEMM_ARGS packed, absmax_q8, scale2, offset, code2, log2_bs, N, K, xp, B, yp, s
     switch ((B + 15) / 16) {
         case 1: if (tall) launch_gemm<1, 2, 8>(NF4_GEMM_ARGS); else launch_gemm<1, 2, 16>(NF4_GEMM_ARGS); break;
-        case 2: if (tall) launch_gemm<2, 4, 8>(NF4_GEMM_ARGS); else launch_gemm<2, 2, 8>(NF4_GEMM_ARGS); break;
+        // 17..32 tokens: the reduction buffer already takes the LDS that the pair table needs, so it is free
+        case 2:
+            if (tall) launch_gemm<2, 4, 8, false, true>(NF4_GEMM_ARGS);
+            else launch_gemm<2, 2, 8, false, true>(NF4_GEMM_ARGS);
+            break;
         case 3: launch_gemm<3, 2, 8>(NF4_GEMM_ARGS); break;
         default: launch_gemm<4, 2, 8>(NF4_GEMM_ARGS); break;
     }
