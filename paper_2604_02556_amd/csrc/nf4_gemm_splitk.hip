@@ -119,7 +119,35 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
         float s2[RG][kH / 2];                    //   64-element quarters lpc and (WIN = 512) lpc + 4
     };
     u32x4 xr[kU];                                // this thread's pieces of the next activation tile
+    // A window that lies inside the split with all its rows inside the matrix -- all but the edges -- is loaded
+    // without predicates from wave-uniform bases plus 32-bit lane offsets (no register pre-sets, no exec-mask
+    // branches, no 64-bit address arithmetic per lane); `small_k` keeps those offsets inside 32 bits.
+    const bool small_k = K <= (int64_t(1) << 26);
+    const bool rows_inside = row0 + 16 * RG <= N;
     auto load_codes = [&](int64_t kw, CodeRegs& cr) {
+        if (small_k && rows_inside && kw + WIN <= k_end) {   // wave-uniform
+            const int64_t u = row0 * K + kw;     // flat index of the wave's first element in the window
+            const uint8_t* cbase = packed + (u >> 1);
+            const int64_t ub = u >> log2_bs;
+            const uint32_t ulow = (uint32_t)(u & ((int64_t(1) << log2_bs) - 1));
+            const uint8_t* qbase = q8 + ub;
+            const float* sbase = scale2 + (ub >> 8);
+            const uint32_t ub_low = (uint32_t)(ub & 255);
+#pragma unroll
+            for (int r = 0; r < RG; ++r) {
+                const uint32_t v = (uint32_t)(16 * r + lrow) * (uint32_t)K;       // elements past u
+#pragma unroll
+                for (int h = 0; h < kH; ++h)
+                    cr.c[r][h] = __builtin_nontemporal_load((const u32x4*)(cbase + ((v >> 1) + 16u * (lpc + 4 * h))));
+#pragma unroll
+                for (int m = 0; m < kH / 2; ++m) {
+                    const uint32_t lb = (ulow + v + 64u * (lpc + 4 * m)) >> log2_bs;   // blocks past ub
+                    cr.qb[r][m] = qbase[lb];
+                    cr.s2[r][m] = sbase[(ub_low + lb) >> 8];
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int r = 0; r < RG; ++r) {
             const int64_t row = row0 + 16 * r + lrow;
@@ -144,6 +172,19 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
         }
     };
     auto load_x = [&](int64_t kw) {
+        if constexpr (kChunks % kThreads == 0) {
+            if (kw + WIN <= k_end) {             // uniform: tokens past B read token B - 1 (their columns are never stored)
+                const _Float16* xbase = x + kw;
+#pragma unroll
+                for (int u = 0; u < kU; ++u) {
+                    const int piece = tid + u * kThreads;
+                    int token = piece / kPiecesPerToken;
+                    token = token < B ? token : B - 1;
+                    xr[u] = *(const u32x4*)(xbase + (int64_t)token * K + 8 * (piece % kPiecesPerToken));
+                }
+                return;
+            }
+        }
 #pragma unroll
         for (int u = 0; u < kU; ++u) {
             const int piece = tid + u * kThreads;
