@@ -1,0 +1,197 @@
+"""GPU parity beyond 2^32 elements: every index, byte offset and block number of
+such a tensor needs 64-bit arithmetic somewhere, and a kernel that keeps one of
+them in 32 bits is right on every ordinary size and wrong here.
+
+Inputs are drawn on the GPU (seeded): random code bytes, random positive scales.
+Each test checks (a) quantisation blocks sampled by the CPU oracle -- the first
+and last ones, the ragged tail, the blocks on both sides of element 2^31 and
+2^32, and random ones -- and (b) EVERY element against a plain PyTorch FP32
+evaluation of the definition (table gather, one multiply, one rounding),
+chunk by chunk on the GPU."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2604_02556_amd import binding as nf4
+from paper_2604_02556_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+N_BIG = (1 << 32) + 3 * 2048 + 77          # more than 2^32 elements, ragged: not a multiple of the tile, odd
+CHUNK = 1 << 27                            # elements per chunk of the PyTorch evaluation
+
+
+def gen(seed):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    return g
+
+
+def random_bytes(count, g):
+    out = torch.empty(count, dtype=torch.uint8, device="cuda")
+    step = 1 << 30
+    for lo in range(0, count, step):       # randint's kernel indexes in 32 bits: fill in pieces
+        hi = min(count, lo + step)
+        out[lo:hi] = torch.randint(0, 256, (hi - lo,), dtype=torch.uint8, device="cuda", generator=g)
+    return out
+
+
+def interesting_blocks(n, seed, count=20_000):
+    nb = (n + 63) // 64
+    rng = np.random.Generator(np.random.PCG64(seed))
+    around = lambda e: np.arange(e // 64 - 4, e // 64 + 4)
+    idx = np.concatenate([np.arange(8), np.arange(nb - 8, nb), around(1 << 31), around(1 << 32),
+                          around((1 << 32) - 2048), rng.integers(0, nb, count)])
+    return np.unique(idx[(idx >= 0) & (idx < nb)])
+
+
+def gather_blocks(packed, out, idx, n):
+    """Host copies of the sampled blocks' code bytes and outputs; the last block may be partial."""
+    codes, outs, lens = [], [], []
+    ti = torch.from_numpy(idx).cuda()
+    full = ti[ti < n // 64]
+    codes.append(packed[: (n // 64) * 32].view(-1, 32)[full].cpu().numpy().reshape(-1))
+    outs.append(out[: (n // 64) * 64].view(torch.int16).view(-1, 64)[full].cpu().numpy().view(np.uint16).reshape(-1))
+    lens += [64] * int(full.numel())
+    if n % 64 and idx[-1] == n // 64:
+        rem = n % 64
+        codes.append(packed[(n // 64) * 32:].cpu().numpy())
+        outs.append(out[(n // 64) * 64: n].view(torch.int16).cpu().numpy().view(np.uint16))
+        lens.append(rem)
+    return codes, outs, lens
+
+
+def torch_definition(packed, scale_of_block, n, tdt, lut):
+    """Yields (first element, reference tensor) per chunk: table[code] * scale rounded once, by PyTorch."""
+    for c0 in range(0, n, CHUNK):
+        cnt = min(CHUNK, n - c0)
+        pk = packed[c0 // 2: (c0 + cnt + 1) // 2]
+        codes = torch.stack([pk >> 4, pk & 15], dim=1).reshape(-1)[:cnt].long()
+        s = scale_of_block(c0 // 64, (c0 + cnt + 63) // 64).repeat_interleave(64)[:cnt]
+        yield c0, (lut[codes] * s).to(tdt)
+
+
+@pytest.mark.parametrize("dq", [False, True])
+def test_dequantize_more_than_2_pow_32_elements(dq):
+    n = N_BIG
+    nb = (n + 63) // 64
+    g = gen(77 + dq)
+    packed = random_bytes((n + 1) // 2, g)
+    lut = torch.from_numpy(oracle.table()).cuda()
+    tdt = torch.bfloat16 if dq else torch.float16
+    odt = oracle.BF16 if dq else oracle.FP16
+    out_whole = torch.full((n + 64,), 0x7A5C, dtype=torch.int16, device="cuda")
+    out = out_whole[:n].view(tdt)
+    idx = interesting_blocks(n, 5 + dq)
+    ti = torch.from_numpy(idx).cuda()
+    if not dq:
+        absmax = torch.rand(nb, device="cuda", generator=g) * 0.2 + 0.001
+        nf4.nf4_dequantize(packed, absmax, 64, n, out)
+        scale_of_block = lambda b0, b1: absmax[b0:b1]
+        scales = absmax[ti].cpu().numpy()
+    else:
+        q8 = random_bytes(nb, g)
+        scale2 = torch.rand((nb + 255) // 256, device="cuda", generator=g) * 0.05 + 0.001
+        offset = torch.tensor([0.07], dtype=torch.float32, device="cuda")
+        code2 = ((torch.arange(256, device="cuda", dtype=torch.float32) - 127.0) / 127.0)
+        nf4.nf4_dequantize_dq(packed, q8, scale2, offset, code2, 64, n, out)
+
+        def scale_of_block(b0, b1):
+            blk = torch.arange(b0, b1, device="cuda")
+            return code2[q8[b0:b1].long()] * scale2[blk >> 8] + offset     # multiply, then add: two roundings
+        # the oracle decodes the sampled scale codes: block j of the sample is put into a group of its own
+        q8_pad = np.zeros(idx.size * 256, np.uint8)
+        q8_pad[::256] = q8[ti].cpu().numpy()
+        scales = oracle.dq_decode(q8_pad, scale2[ti >> 8].cpu().numpy(), offset.cpu().numpy(),
+                                  code2.cpu().numpy())[::256].copy()
+    torch.cuda.synchronize()
+    assert bool((out_whole[n:] == 0x7A5C).all().item()), "wrote past the last element"
+
+    # (a) the oracle on sampled blocks
+    codes, outs, lens = gather_blocks(packed, out, idx, n)
+    full_cnt = sum(1 for l in lens if l == 64)
+    want = oracle.dequantize(codes[0], scales[:full_cnt], 64 * full_cnt, out_dtype=odt)
+    assert np.array_equal(want, outs[0]), "sampled full blocks differ from the oracle"
+    assert len(codes) == 2                                   # the ragged last block is in the sample
+    want = oracle.dequantize(codes[1], scales[full_cnt:], lens[-1], out_dtype=odt)
+    assert np.array_equal(want, outs[1]), "the ragged last block differs from the oracle"
+
+    # (b) every element against PyTorch's evaluation of the definition
+    for c0, ref in torch_definition(packed, scale_of_block, n, tdt, lut):
+        got = out[c0: c0 + ref.numel()]
+        assert torch.equal(got.view(torch.int16), ref.view(torch.int16)), f"chunk at element {c0} differs"
+
+
+@pytest.mark.parametrize("tuned", [False, True])
+def test_quantize_more_than_2_pow_32_elements(tuned):
+    """Both quantisers on a tensor of more than 2^32 elements: every block's scale against a PyTorch
+    reduction, and the codes and scales of sampled blocks (and of the ragged last one) against the oracle."""
+    n = (1 << 32) + 5 * 64 + 9
+    nb = (n + 63) // 64
+    src = torch.empty(n, dtype=torch.float32, device="cuda")
+    g = gen(91)
+    for lo in range(0, n, 1 << 30):
+        hi = min(n, lo + (1 << 30))
+        src[lo:hi].normal_(0.0, 0.015, generator=g)
+    bufs = nf4.alloc_quantized(n)
+    if tuned:
+        nf4.nf4_quantize(src, n, 64, bufs["packed"], bufs["absmax"])
+    else:
+        nf4.nf4_quantize_ref(src, n, 64, bufs["packed"], bufs["absmax"])
+    torch.cuda.synchronize()
+    # every scale: max |x| of the block
+    full = n // 64
+    want = src[: full * 64].view(-1, 64).abs().amax(dim=1)
+    assert torch.equal(bufs["absmax"][:full], want)
+    assert float(bufs["absmax"][full]) == float(src[full * 64:].abs().max())
+    # sampled blocks: codes and scales from the oracle
+    idx = interesting_blocks(n, 17, count=5_000)
+    idx = idx[idx < full]
+    ti = torch.from_numpy(idx).cuda()
+    blocks = src[: full * 64].view(-1, 64)[ti].cpu().numpy().reshape(-1)
+    p, a = oracle.quantize(blocks)
+    assert np.array_equal(p, bufs["packed"][: full * 32].view(-1, 32)[ti].cpu().numpy().reshape(-1))
+    assert np.array_equal(a, bufs["absmax"][ti].cpu().numpy())
+    tail = src[full * 64:].cpu().numpy()
+    p, a = oracle.quantize(tail)
+    assert np.array_equal(p, bufs["packed"][full * 32:].cpu().numpy()) and a[0] == float(bufs["absmax"][full])
+
+
+@pytest.mark.parametrize("B", [1, 4, 16])
+def test_gemv_and_gemm_on_a_matrix_of_more_than_2_pow_32_weights(B):
+    """N x K > 2^32: sampled rows (first, last, and those whose flat index crosses 2^31 and 2^32) against the
+    oracle, for the GEMV and for both algorithms of the GEMM."""
+    N, K = 32768 + 48, 131072 + 64
+    n = N * K
+    assert n > (1 << 32)
+    nb = n // 64
+    g = gen(123)
+    packed = random_bytes(n // 2, g)
+    q8 = random_bytes(nb, g)
+    scale2 = torch.rand((nb + 255) // 256, device="cuda", generator=g) * 0.02 + 0.001
+    offset = torch.tensor([0.03], dtype=torch.float32, device="cuda")
+    code2 = ((torch.arange(256, device="cuda", dtype=torch.float32) - 127.0) / 127.0)
+    x = torch.from_numpy(synth.activations_fp16(B, K, seed=B + 40)).cuda()
+    yv = torch.full((B, N), float("nan"), dtype=torch.float16, device="cuda")
+    ym = torch.full((B, N), float("nan"), dtype=torch.float16, device="cuda")
+    ys = torch.full((B, N), float("nan"), dtype=torch.float16, device="cuda")
+    ws = torch.empty(nf4.nf4_dequant_gemm_workspace_bytes(N, K, B), dtype=torch.uint8, device="cuda")
+    nf4.nf4_dequant_gemv(packed, q8, scale2, offset, code2, 64, N, K, x, B, yv)
+    nf4.nf4_dequant_gemm(packed, q8, scale2, offset, code2, 64, N, K, x, B, ym)
+    nf4.nf4_dequant_gemm(packed, q8, scale2, offset, code2, 64, N, K, x, B, ys, workspace=ws)
+    torch.cuda.synchronize()
+    for y in (yv, ym, ys):
+        assert not bool(torch.isnan(y).any().item())
+
+    hp, hq, hs = packed.cpu().numpy(), q8.cpu().numpy(), scale2.cpu().numpy()
+    ho, hc, hx = offset.cpu().numpy(), code2.cpu().numpy(), x.cpu().numpy().view(np.uint16)
+    r31, r32 = (1 << 31) // K, (1 << 32) // K
+    for r0 in (0, r31 - 1, r32 - 1, N - 3):
+        cnt = 3
+        _, ref_v = oracle.dequant_gemv_rows(hp, hq, hs, ho, hc, N, K, hx, r0, cnt)
+        _, ref_m = oracle.dequant_gemm_rows(hp, hq, hs, ho, hc, N, K, hx, r0, cnt)
+        rms = max(float(np.sqrt(np.mean(ref_v ** 2))), 1e-6)
+        for y, ref, what in ((yv, ref_v, "gemv"), (ym, ref_m, "gemm"), (ys, ref_m, "gemm split-K")):
+            got = y[:, r0:r0 + cnt].cpu().numpy().astype(np.float64)
+            assert np.all(np.abs(got - ref) <= 1e-2 * np.abs(ref) + 1e-2 * rms), (what, r0)
