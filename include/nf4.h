@@ -101,7 +101,11 @@ int nf4_dequant_gemv(const uint8_t* packed, const uint8_t* absmax_q8, const floa
  * III-C: dequantise W to FP16, then an FP16 matmul with FP32 accumulation)
  * without the FP16 copy of W in memory:
  *   y[b][r] = rne_fp16( sum_k x[b][k] * W16[r][k] ),
- *   W16[r][k] = rne_fp16( level[code(r*K + k)] * scale((r*K + k) / blocksize) ).
+ *   W16[r][k] = rne_fp16( level[code(r*K + k)] * scale((r*K + k) / blocksize) ),
+ * the exact product narrowed in one rounding.  (nf4_dequantize_dq rounds the
+ * product to FP32 first; its FP16 result differs from W16 by one FP16 ulp where
+ * that FP32 value lies exactly between two FP16 values, about 1 weight in 10^4
+ * to 10^5.)
  * Same arguments and layouts as nf4_dequant_gemv; 1 <= B <= 64, K > 0 and
  * K % blocksize == 0 (else NF4_ERR_SHAPE).  packed and x 16-byte aligned.
  *

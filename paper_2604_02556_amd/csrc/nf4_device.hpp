@@ -64,11 +64,15 @@ __device__ __forceinline__ uint32_t pack2<NF4_BF16>(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, h);
 }
 
-// rne_fp16(rne_fp32(a * s)) for two values, packed (`lo` product in the low half).
-// Written as a fused multiply-add with a -0 addend: a * s + (-0) is the rounded
-// FP32 product with its sign of zero kept, and the compiler turns the FP32 FMA
-// followed by the narrowing into one mixed-precision instruction per value
-// (v_fma_mixlo_f16 / v_fma_mixhi_f16) instead of multiply, multiply, convert.
+// rne_fp16(a * s) for two values, packed (`lo` product in the low half): the exact
+// product narrowed to FP16 in ONE rounding.  Written as a fused multiply-add with
+// a -0 addend (a * s + (-0) keeps the product's sign of zero), which the compiler
+// turns into one mixed-precision instruction per value (v_fma_mixlo_f16 /
+// v_fma_mixhi_f16) instead of multiply, multiply, convert.  A multiply followed
+// by a convert rounds twice (to FP32, then to FP16); the two results differ, by
+// one FP16 ulp, only where the FP32-rounded product lies exactly half way between
+// two FP16 values -- about one product in 10^4 to 10^5.  Kernels whose output must
+// equal that two-step result bit for bit (the dequantiser) do not use this.
 // `neg_zero` must come from opaque_neg_zero(): a visible constant would let the
 // compiler fold the FMA back into a multiply.
 __device__ __forceinline__ float opaque_neg_zero() {
@@ -81,9 +85,9 @@ __device__ __forceinline__ uint32_t scaled_pack2_f16(float lo, float hi, float s
     return __builtin_bit_cast(uint32_t, h);
 }
 
-// The FP32 product a * s carried as two FP16 terms for the matrix cores:
-// hi = rne_fp16(a * s), lo = rne_fp16(a * s - hi) (one fused operation, so the
-// residual is formed from the exact product).  hi + lo reproduces the product to
+// The product a * s carried as two FP16 terms for the matrix cores:
+// hi = rne_fp16(a * s) (the exact product, one rounding), lo = rne_fp16(a * s - hi)
+// (one fused operation, so the residual is formed from the exact product).  hi + lo reproduces the product to
 // about 2^-22 relative (2^-25 absolute where lo is an FP16 subnormal); it needs
 // |a * s| < 65504.  Two mixed-precision instructions per value.
 __device__ __forceinline__ void two_term_pack2_f16(float a0, float a1, float s, float neg_zero, uint32_t& hi,
