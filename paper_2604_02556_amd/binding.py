@@ -15,6 +15,15 @@ _DTYPE_CODE = {torch.float16: NF4_FP16, torch.bfloat16: NF4_BF16}
 
 _lib = None
 
+NF4_BATCH_MAX = 8
+
+
+class Nf4Tensor(ctypes.Structure):
+    """nf4_tensor of include/nf4.h: one tensor of a batched dequantisation (device addresses)."""
+    _fields_ = [("packed", ctypes.c_void_p), ("absmax", ctypes.c_void_p), ("absmax_q8", ctypes.c_void_p),
+                ("scale2", ctypes.c_void_p), ("offset", ctypes.c_void_p), ("code2", ctypes.c_void_p),
+                ("out", ctypes.c_void_p), ("n", ctypes.c_int64)]
+
 
 class NF4Error(RuntimeError):
     def __init__(self, status, name, hip_error=0):
@@ -38,6 +47,7 @@ def lib():
     L.nf4_dequantize.argtypes = [vp, vp, i32, i64, vp, i32, vp]
     L.nf4_dequantize_dq.argtypes = [vp, vp, vp, vp, vp, i32, i64, vp, i32, vp]
     L.nf4_dequant_gemv.argtypes = [vp, vp, vp, vp, vp, i32, i64, i64, vp, i32, vp, vp]
+    L.nf4_dequantize_batch.argtypes = [c.POINTER(Nf4Tensor), i32, i32, i32, vp]
     L.nf4_dequant_gemm.argtypes = [vp, vp, vp, vp, vp, i32, i64, i64, vp, i32, vp, vp, c.c_size_t, vp]
     L.nf4_dequant_gemm.restype = i32
     L.nf4_dequant_gemm_workspace_bytes.argtypes = [i64, i64, i32]
@@ -121,6 +131,23 @@ def nf4_quantize_ref_codebook(src, n, blocksize, codebook, dq_group, packed, abs
     _check(lib().nf4_quantize_ref_codebook(_ptr(src), n, blocksize, _ptr(codebook), dq_group, _ptr(packed),
                                            _ptr(absmax), _ptr(absmax_q8), _ptr(scale2), _ptr(offset), _ptr(code2),
                                            _stream(stream)))
+
+
+def nf4_dequantize_batch(tensors, blocksize, stream=None):
+    """One launch for up to NF4_BATCH_MAX tensors.  tensors: dicts with packed, out (a torch tensor whose dtype
+    picks FP16 or BF16, the same for all), n, and either absmax or absmax_q8 + scale2 + offset + code2."""
+    items = (Nf4Tensor * max(len(tensors), 1))()
+    dtypes = set()
+    for it, t in zip(items, tensors):
+        it.packed, it.absmax = _ptr(t["packed"]), _ptr(t.get("absmax"))
+        it.absmax_q8, it.scale2 = _ptr(t.get("absmax_q8")), _ptr(t.get("scale2"))
+        it.offset, it.code2 = _ptr(t.get("offset")), _ptr(t.get("code2"))
+        it.out, it.n = _ptr(t["out"]), t["n"]
+        dtypes.add(t["out"].dtype)
+    if len(dtypes) > 1:
+        raise ValueError("all outputs of a batch must have one dtype")
+    dt = _DTYPE_CODE[next(iter(dtypes))] if dtypes else NF4_FP16
+    _check(lib().nf4_dequantize_batch(items, len(tensors), blocksize, dt, _stream(stream)))
 
 
 def nf4_dequant_gemv(packed, absmax_q8, scale2, offset, code2, blocksize, N, K, x, B, y, stream=None):

@@ -74,14 +74,14 @@ __device__ __forceinline__ float dq_scale(const ScaleArgs& a, float offset, int6
     return prod + offset;
 }
 
+// The work of one single-wave workgroup: tile `t` of a tensor with `tiles` full tiles, or (t == tiles) its
+// ragged end.
 template <int DT, bool DQ>
-__global__ __launch_bounds__(kWave) void dequant_kernel(const uint8_t* __restrict__ packed, ScaleArgs sa,
-                                                        int log2_bs, int64_t n, int64_t tiles,
-                                                        uint16_t* __restrict__ out) {
+__device__ __forceinline__ void dequant_group(const uint8_t* __restrict__ packed, const ScaleArgs& sa, int log2_bs,
+                                              int64_t n, int64_t tiles, uint16_t* __restrict__ out, int64_t t) {
     __shared__ uint32_t stage[kTileBytes / 4];
     __shared__ float lut[16];
     const int lane = threadIdx.x;
-    const int64_t t = blockIdx.x;
     const float offset = DQ ? sa.offset[0] : 0.0f;
     // the table: instruction literals for NF4, 64 bytes from memory for a caller's codebook (Sec. V-A: the
     // data type is a parameter); either way ordered by the fence below
@@ -142,6 +142,54 @@ __global__ __launch_bounds__(kWave) void dequant_kernel(const uint8_t* __restric
             }
         }
     }
+}
+
+template <int DT, bool DQ>
+__global__ __launch_bounds__(kWave) void dequant_kernel(const uint8_t* __restrict__ packed, ScaleArgs sa,
+                                                        int log2_bs, int64_t n, int64_t tiles,
+                                                        uint16_t* __restrict__ out) {
+    dequant_group<DT, DQ>(packed, sa, log2_bs, n, tiles, out, blockIdx.x);
+}
+
+// Several tensors in one launch: workgroup g belongs to the tensor i with first_group[i] <= g <
+// first_group[i + 1], in the order given, so the write frontier still moves through one tensor after the other.
+// One launch pays the fill and drain of the load -> store pipeline once instead of once per tensor.
+struct BatchArgs {
+    const uint8_t* packed[NF4_BATCH_MAX];
+    const float* absmax[NF4_BATCH_MAX];
+    const uint8_t* q8[NF4_BATCH_MAX];
+    const float* scale2[NF4_BATCH_MAX];
+    const float* offset[NF4_BATCH_MAX];
+    const float* code2[NF4_BATCH_MAX];
+    uint16_t* out[NF4_BATCH_MAX];
+    int64_t n[NF4_BATCH_MAX];
+    int64_t tiles[NF4_BATCH_MAX];
+    int64_t first_group[NF4_BATCH_MAX + 1];
+    int count;
+};
+
+template <int DT, bool DQ>
+__global__ __launch_bounds__(kWave) void dequant_batch_kernel(BatchArgs ba, int log2_bs) {
+    const int64_t g = blockIdx.x;
+    int i = 0;
+#pragma unroll
+    for (int k = 1; k < NF4_BATCH_MAX; ++k)
+        if (k < ba.count && g >= ba.first_group[k]) i = k;             // wave-uniform
+    // select by comparison rather than by indexing, so that the argument arrays stay in scalar registers
+    const uint8_t* packed = ba.packed[0];
+    ScaleArgs sa = {ba.absmax[0], ba.q8[0], ba.scale2[0], ba.offset[0], ba.code2[0], 8, nullptr};
+    uint16_t* out = ba.out[0];
+    int64_t n = ba.n[0], tiles = ba.tiles[0], first = ba.first_group[0];
+#pragma unroll
+    for (int k = 1; k < NF4_BATCH_MAX; ++k)
+        if (i == k) {
+            packed = ba.packed[k];
+            sa.absmax = ba.absmax[k]; sa.q8 = ba.q8[k]; sa.scale2 = ba.scale2[k]; sa.offset = ba.offset[k];
+            sa.code2 = ba.code2[k];
+            out = ba.out[k];
+            n = ba.n[k]; tiles = ba.tiles[k]; first = ba.first_group[k];
+        }
+    dequant_group<DT, DQ>(packed, sa, log2_bs, n, tiles, out, g - first);
 }
 
 template <bool DQ>
@@ -206,4 +254,55 @@ extern "C" int nf4_dequantize_dq_codebook(const uint8_t* packed, const uint8_t* 
     if (log2_group < 0) return NF4_ERR_SHAPE;
     nf4::ScaleArgs sa = {nullptr, absmax_q8, scale2, offset, code2, log2_group, codebook};
     return nf4::launch<true>(packed, sa, blocksize, n, out, out_dtype, stream);
+}
+
+extern "C" int nf4_dequantize_batch(const nf4_tensor* tensors, int count, int blocksize, int out_dtype,
+                                    void* stream) {
+    using namespace nf4;
+    if (count < 0 || count > NF4_BATCH_MAX) return NF4_ERR_SIZE;
+    const int log2_bs = log2_blocksize(blocksize);
+    if (log2_bs < 0) return NF4_ERR_BLOCKSIZE;
+    if (out_dtype != NF4_FP16 && out_dtype != NF4_BF16) return NF4_ERR_DTYPE;
+    if (count == 0) return NF4_OK;
+    if (!tensors) return NF4_ERR_NULL;
+    BatchArgs ba = {};
+    int64_t groups = 0;
+    bool dq = false, kind_known = false;
+    for (int i = 0; i < count; ++i) {
+        const nf4_tensor& t = tensors[i];
+        if (t.n < 0) return NF4_ERR_SIZE;
+        if (t.n == 0) continue;                              // an empty tensor takes no part
+        if (!t.packed || !t.out) return NF4_ERR_NULL;
+        const bool this_dq = t.absmax == nullptr;
+        if (this_dq) {
+            if (!t.absmax_q8 || !t.scale2 || !t.offset || !t.code2) return NF4_ERR_NULL;
+            if (!aligned(t.scale2, 4) || !aligned(t.offset, 4) || !aligned(t.code2, 4)) return NF4_ERR_ALIGN;
+        } else if (!aligned(t.absmax, 4)) {
+            return NF4_ERR_ALIGN;
+        }
+        if (!aligned(t.packed, 16) || !aligned(t.out, 16)) return NF4_ERR_ALIGN;
+        if (kind_known && this_dq != dq) return NF4_ERR_SHAPE;       // one kind of scales per call
+        dq = this_dq;
+        kind_known = true;
+        const int k = ba.count++;
+        ba.packed[k] = t.packed; ba.absmax[k] = t.absmax; ba.q8[k] = t.absmax_q8; ba.scale2[k] = t.scale2;
+        ba.offset[k] = t.offset; ba.code2[k] = t.code2; ba.out[k] = (uint16_t*)t.out;
+        ba.n[k] = t.n;
+        ba.tiles[k] = t.n / kTileElems;
+        ba.first_group[k] = groups;
+        groups += ba.tiles[k] + (t.n % kTileElems != 0 ? 1 : 0);
+        ba.first_group[k + 1] = groups;
+    }
+    if (ba.count == 0) return NF4_OK;
+    if (groups > 0x7fffffffLL) return NF4_ERR_SIZE;
+    hipStream_t s = (hipStream_t)stream;
+    const dim3 grid((unsigned)groups), block(kWave);
+    if (out_dtype == NF4_FP16) {
+        if (dq) hipLaunchKernelGGL((dequant_batch_kernel<NF4_FP16, true>), grid, block, 0, s, ba, log2_bs);
+        else hipLaunchKernelGGL((dequant_batch_kernel<NF4_FP16, false>), grid, block, 0, s, ba, log2_bs);
+    } else {
+        if (dq) hipLaunchKernelGGL((dequant_batch_kernel<NF4_BF16, true>), grid, block, 0, s, ba, log2_bs);
+        else hipLaunchKernelGGL((dequant_batch_kernel<NF4_BF16, false>), grid, block, 0, s, ba, log2_bs);
+    }
+    return record_hip(hipGetLastError());
 }

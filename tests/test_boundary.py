@@ -30,7 +30,7 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(L):
     names = declared_functions()
     assert set(names) >= {"nf4_dequantize", "nf4_dequantize_dq", "nf4_dequant_gemv", "nf4_quantize_ref",
-                          "nf4_quantize", "nf4_dequant_gemm", "nf4_dequant_gemm_workspace_bytes", "nf4_dequantize_codebook",
+                          "nf4_quantize", "nf4_dequant_gemm", "nf4_dequant_gemm_workspace_bytes", "nf4_dequantize_batch", "nf4_dequantize_codebook",
                           "nf4_dequantize_dq_codebook", "nf4_quantize_ref_codebook", "nf4_last_hip_error", "nf4_status_string"}
     for name in names:
         assert hasattr(L, name), name
@@ -108,6 +108,34 @@ def test_gemm_argument_checks(L):
     need = L.nf4_dequant_gemm_workspace_bytes(4096, 8192, 64)
     assert need >= 2 * 64 * 4096 * 4                      # at least two splits of FP32 partial sums
     assert f(*a, 64, 4096, 8192, P, 64, P, P, need - 1, None) == E_SIZE
+
+
+def test_dequantize_batch_argument_checks(L):
+    T = binding.Nf4Tensor
+
+    def call(items, count=None, bs=64, dt=0):
+        arr = (T * max(len(items), 1))(*items)
+        return L.nf4_dequantize_batch(arr, len(items) if count is None else count, bs, dt, None)
+    fp32 = lambda n=5, packed=P, absmax=P, out=P: T(packed, absmax, None, None, None, None, out, n)
+    dq = lambda n=5, q8=P, s2=P, off=P, c2=P: T(P, None, q8, s2, off, c2, P, n)
+    assert call([]) == OK
+    assert L.nf4_dequantize_batch(None, 0, 64, 0, None) == OK
+    assert L.nf4_dequantize_batch(None, 2, 64, 0, None) == E_NULL
+    assert call([fp32()], count=-1) == E_SIZE
+    assert call([fp32()], count=binding.NF4_BATCH_MAX + 1) == E_SIZE
+    assert call([fp32()], bs=48) == E_BS
+    assert call([fp32()], dt=2) == E_DT
+    assert call([fp32(n=-1)]) == E_SIZE
+    assert call([fp32(n=0), fp32(n=0, packed=None, out=None)]) == OK      # empty tensors are skipped unchecked
+    assert call([fp32(packed=None)]) == E_NULL
+    assert call([fp32(out=None)]) == E_NULL
+    assert call([fp32(out=P + 2)]) == E_ALIGN
+    assert call([fp32(packed=P + 8)]) == E_ALIGN
+    assert call([fp32(absmax=P + 2)]) == E_ALIGN
+    assert call([dq(q8=None)]) == E_NULL
+    assert call([dq(c2=None)]) == E_NULL
+    assert call([dq(s2=P + 1)]) == E_ALIGN
+    assert call([fp32(n=0), fp32(), dq()]) == E_SHAPE                      # two kinds of scales in one call
 
 
 def test_gemm_workspace_bytes_of_rejected_shapes_is_zero(L):
