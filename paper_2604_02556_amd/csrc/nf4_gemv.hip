@@ -8,9 +8,11 @@
 // wave64 DPP reductions, the kernel of this file.  From 7 tokens on the entry
 // point hands the same sum to the matrix-core kernel of nf4_gemm.hip with the
 // FP32 weight carried as two FP16 terms.  Layout of the work here:
-//   * one wave (a single-wave workgroup, one-shot grid) owns R consecutive rows
-//     of W over the whole of K, so no partial sums ever leave the wave and the
-//     summation order is fixed (deterministic results);
+//   * one wave owns R consecutive rows of W over the whole of K, so no partial
+//     sums ever leave the wave and the summation order is fixed (deterministic
+//     results); the grid is one-shot.  Short rows: single-wave workgroups
+//     (gemv_kernel).  Long rows (K >= 16384): eight waves per workgroup, which
+//     share one table (gemv_pair_kernel);
 //   * per step lane l owns CH consecutive dwords of codes of each row (8*CH
 //     elements, always inside one quantisation block): one 128-bit (CH=4) or
 //     64-bit (CH=2) load per row, contiguous across the wave.  The loads of
@@ -18,8 +20,10 @@
 //   * its 8*CH activations per token stay FP16 in registers and enter the FP32
 //     multiply-add directly (mixed-precision FMA), reused for all R rows;
 //   * levels come from a 16-entry LDS table written from literals (no bank
-//     conflicts, see nf4_dequant.hip); the double-quantisation map code2 sits
-//     in 1 KiB of LDS;
+//     conflicts, see nf4_dequant.hip) or, in the eight-wave form, from the
+//     byte-indexed pair table (issue_pair_lookups: one permute and one 64-bit
+//     read per two weights); the double-quantisation map code2 sits in 1 KiB
+//     of LDS;
 //   * the block scale is applied once per lane chunk (sum of level*x first,
 //     then one multiply-add by the scale), not once per element;
 //   * addresses of the level table are taken four at a time: two masked copies
@@ -229,10 +233,135 @@ __global__ __launch_bounds__(kWave, 2) void gemv_kernel(const uint8_t* __restric
         }
 }
 
+// ---- the same kernel for long rows: eight waves per workgroup share the 64 KiB byte-pair table, which cuts a
+// third of the instructions per weight.  Building the table once per workgroup pays when a wave has many steps
+// (measured on MI355X, 1 to 6 tokens: K = 28672 -> 7-18 % faster, K = 8192 -> 9-17 % slower).  The two kernels
+// are kept apart on purpose: the single-wave one is bound by instruction issue and loses 6 % to a few more
+// instructions in front of its loop.
+constexpr int kPairWaves = 8;
+constexpr int64_t kPairMinK = 16384;
+
+template <int B, int CH, int R>
+__device__ __forceinline__ void compute_step_pair(const StepRegs<B, CH, R>& g, const uint8_t* table,
+                                                  uint32_t lane_off, const float* code2_lds, float offset,
+                                                  float (&acc)[R][B]) {
+    constexpr int U = R * CH;
+    float c2[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) c2[r] = code2_lds[g.q8[r]];
+    float lv[2][8];
+    issue_pair_lookups(g.q[0][0], table, lane_off, lv[0]);
+    float part[B];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {                                  // software pipeline, depth 2
+        const int r = u / CH, c = u % CH;
+        if (u + 1 < U) {
+            issue_pair_lookups(g.q[(u + 1) / CH][(u + 1) % CH], table, lane_off, lv[(u + 1) & 1]);
+            lds_wait<4>();                                         // everything but the 4 just issued has landed
+        } else {
+            lds_wait<0>();
+        }
+        if (c == 0) {
+#pragma unroll
+            for (int b = 0; b < B; ++b) part[b] = 0.0f;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int b = 0; b < B; ++b) part[b] = __builtin_fmaf(lv[u & 1][j], (float)g.xh[b][c][j], part[b]);
+        if (c == CH - 1) {
+            const float prod = c2[r] * g.s2[r];                    // rounded product, then rounded sum
+            const float s = prod + offset;
+#pragma unroll
+            for (int b = 0; b < B; ++b) acc[r][b] = __builtin_fmaf(s, part[b], acc[r][b]);
+        }
+    }
+}
+
+template <int B, int CH, int R, bool FULL>
+__global__ __launch_bounds__(kPairWaves * kWave) void gemv_pair_kernel(const uint8_t* __restrict__ packed,
+                                                                       const uint8_t* __restrict__ q8,
+                                                                       const float* __restrict__ scale2,
+                                                                       const float* __restrict__ offset_p,
+                                                                       const float* __restrict__ code2, int log2_bs,
+                                                                       int64_t N, int64_t K,
+                                                                       const _Float16* __restrict__ x,
+                                                                       _Float16* __restrict__ y) {
+    constexpr int E = 8 * CH;
+    constexpr int kSlice = E * kWave;
+    constexpr int kThreads = kPairWaves * kWave;
+    // one LDS object, so that the pair table sits at address 0: table | 16 levels | code2
+    __shared__ __attribute__((aligned(16))) uint8_t smem[kPairTableBytes + 64 + 1024];
+    float* lut = (float*)(smem + kPairTableBytes);
+    float* code2_lds = (float*)(smem + kPairTableBytes + 64);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    if (tid < 16) lut[tid] = __uint_as_float(level_literal(tid));
+    for (int i = tid; i < 256; i += kThreads) code2_lds[i] = code2[i];
+    __syncthreads();
+    fill_pair_table((float2_t*)smem, lut, tid, kThreads);
+    __syncthreads();
+    const float offset = offset_p[0];
+    const uint32_t lane_off = pair_lane_offset(lane);
+
+    const int64_t r0 = ((int64_t)blockIdx.x * kPairWaves + wave) * R;
+    if (r0 >= N) return;                      // a whole wave past the last row; no barrier follows
+    const int rows = (N - r0) < R ? (int)(N - r0) : R;
+
+    float acc[R][B];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int b = 0; b < B; ++b) acc[r][b] = 0.0f;
+
+    const int64_t steps = (K + kSlice - 1) / kSlice;
+    RowBases<R> rb;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int64_t row_start = (r0 + (r < rows ? r : 0)) * K;   // rows past N alias row r0 and are never read
+        const int64_t row_blk = row_start >> log2_bs;
+        rb.codes[r] = packed + (row_start >> 1);
+        rb.q8[r] = q8 + row_blk;
+        rb.blk_lo[r] = (uint32_t)(row_blk & 255);
+        rb.s2[r] = scale2 + (row_blk >> 8);
+    }
+    StepRegs<B, CH, R> ping, pong;
+    load_step<B, CH, R, FULL>(ping, rb, x, log2_bs, K, rows, 0, lane);
+    for (int64_t it = 0;;) {
+        if (it + 1 < steps) load_step<B, CH, R, FULL>(pong, rb, x, log2_bs, K, rows, (it + 1) * kSlice, lane);
+        compute_step_pair<B, CH, R>(ping, smem, lane_off, code2_lds, offset, acc);
+        if (++it >= steps) break;
+        if (it + 1 < steps) load_step<B, CH, R, FULL>(ping, rb, x, log2_bs, K, rows, (it + 1) * kSlice, lane);
+        compute_step_pair<B, CH, R>(pong, smem, lane_off, code2_lds, offset, acc);
+        if (++it >= steps) break;
+    }
+
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int b = 0; b < B; ++b) {
+            const float total = wave_sum_to_lane63(acc[r][b]);
+            if (lane == kWave - 1 && r < rows) y[(int64_t)b * N + r0 + r] = (_Float16)total;
+        }
+}
+
 template <int B, int CH, int R>
 static void launch_gemv(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
                         const float* code2, int log2_bs, int64_t N, int64_t K, const void* x, void* y,
                         hipStream_t s) {
+    if (K >= kPairMinK) {
+        const unsigned pair_groups = (unsigned)((N + R * kPairWaves - 1) / (R * kPairWaves));
+        if (K % (8 * CH * kWave) == 0 && N % R == 0)
+            hipLaunchKernelGGL((gemv_pair_kernel<B, CH, R, true>), dim3(pair_groups), dim3(kPairWaves * kWave), 0, s,
+                               packed, q8, scale2, offset, code2, log2_bs, N, K, (const _Float16*)x, (_Float16*)y);
+        else
+            hipLaunchKernelGGL((gemv_pair_kernel<B, CH, R, false>), dim3(pair_groups), dim3(kPairWaves * kWave), 0,
+                               s, packed, q8, scale2, offset, code2, log2_bs, N, K, (const _Float16*)x,
+                               (_Float16*)y);
+        return;
+    }
     const unsigned groups = (unsigned)((N + R - 1) / R);
     if (K % (8 * CH * kWave) == 0 && N % R == 0)
         hipLaunchKernelGGL((gemv_kernel<B, CH, R, true>), dim3(groups), dim3(kWave), 0, s, packed, q8, scale2,

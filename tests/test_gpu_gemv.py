@@ -38,7 +38,8 @@ def within_bar(y, ref):
 
 
 @pytest.mark.parametrize("B", [1, 2, 3, 4, 5, 6, 7, 8, 11, 16])
-@pytest.mark.parametrize("N,K", [(37, 256), (64, 2048 + 512), (9, 8192), (130, 64)])
+@pytest.mark.parametrize("N,K", [(37, 256), (64, 2048 + 512), (9, 8192), (130, 64),
+                                 (37, 16384), (41, 18496), (4, 32768)])      # K >= 16384: the eight-wave kernel
 def test_small_shapes_all_batches(N, K, B):
     case = make_case(N, K, seed=N * 7 + K)
     x = synth.activations_fp16(B, K, seed=B)
@@ -61,6 +62,23 @@ def test_unit_vectors_reproduce_columns_of_dequantized_w():
             x[b, k] = 1.0
         y = gemv_gpu(case, N, K, x)
         want = w[:, chunk].T.astype(np.float16)          # one product, one rounding: exact
+        assert np.array_equal(y.view(np.uint16), want.view(np.uint16))
+
+
+def test_unit_vectors_on_long_rows():
+    """The same property through the eight-wave kernel that serves rows of 16384 elements and more (a ragged
+    last step and a row count that leaves most waves of the last workgroup without rows)."""
+    N, K = 35, 16384 + 2048 + 192
+    case = make_case(N, K, seed=21)
+    w = oracle.dequantize_dq(*case, N * K, out_dtype=oracle.FP32).reshape(N, K)
+    ks = [0, 1, 63, 64, 2047, 2048, 16383, 16384, K - 193, K - 192, K - 65, K - 1]
+    for k0 in range(0, len(ks), 4):
+        chunk = ks[k0:k0 + 4]
+        x = np.zeros((len(chunk), K), np.float16)
+        for b, k in enumerate(chunk):
+            x[b, k] = 1.0
+        y = gemv_gpu(case, N, K, x)
+        want = w[:, chunk].T.astype(np.float16)
         assert np.array_equal(y.view(np.uint16), want.view(np.uint16))
 
 
