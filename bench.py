@@ -33,7 +33,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
-FP32_FMA_PEAK_TFLOPS = 78.6                         # 256 CUs x 64 lanes x 2.4 GHz x 2, plain (unpacked) FP32 FMA
+FP32_FMA_PEAK_TFLOPS = 157.3                        # FP32 vector peak: 256 CUs x 4 SIMDs x 32 lanes x 2 flop x 2.4 GHz
 BYTES_PER_ELEM = 0.5 + 4.0 / 64.0 + 2.0            # codes + fp32 absmax read, 16-bit value written
 BYTES_PER_ELEM_DQ = 0.5 + 1.0 / 64.0 + 4.0 / 16384.0 + 2.0
 GEMV_BYTES_PER_ELEM = 0.5 + 1.0 / 64.0 + 4.0 / 16384.0
