@@ -126,6 +126,33 @@ def test_config3_llama33_70b_layer_streamed_into_one_buffer():
         check_block_extremes(view, bufs["absmax"], torch.float16)
 
 
+def test_config3_llama33_70b_layer_in_one_launch():
+    """The seven projections of a 70B-shaped layer through nf4_dequantize_batch into a layer-sized arena, as
+    bench.py's one-launch-per-layer figure does it: bit-equal to seven separate calls (which the test above ties
+    to the oracle), block extremes checked on every block."""
+    shapes = synth.LLAMA33_70B
+    items, refs, offs, total = [], [], [], 0
+    for name, shape in shapes.items():
+        offs.append(total)
+        total += (synth.numel(shape) + 127) // 128 * 128
+    arena = torch.empty(total, dtype=torch.float16, device="cuda")
+    for ti, ((name, shape), off) in enumerate(zip(shapes.items(), offs)):
+        n = synth.numel(shape)
+        w = draw(n, synth.LLAMA33_70B_SIGMA, 3000 + ti)
+        bufs = nf4.alloc_quantized(n)
+        nf4.nf4_quantize_ref(w, n, 64, bufs["packed"], bufs["absmax"])
+        del w
+        items.append(dict(packed=bufs["packed"], absmax=bufs["absmax"], out=arena[off:off + n], n=n))
+    nf4.nf4_dequantize_batch(items, 64)
+    torch.cuda.synchronize()
+    single = torch.empty(max(it["n"] for it in items), dtype=torch.float16, device="cuda")
+    for it in items:
+        nf4.nf4_dequantize(it["packed"], it["absmax"], 64, it["n"], single)
+        torch.cuda.synchronize()
+        assert torch.equal(it["out"].view(torch.int16), single[:it["n"]].view(torch.int16))
+        check_block_extremes(it["out"], it["absmax"], torch.float16)
+
+
 @pytest.mark.parametrize("N,K", synth.GEMV_SHAPES)
 def test_config4_gemv_70b_mlp_shapes(N, K):
     n = N * K

@@ -37,7 +37,9 @@ def test_captured_calls_replay_bit_exactly():
     ws = torch.empty(nf4.nf4_dequant_gemm_workspace_bytes(N, K, B), dtype=torch.uint8, device="cuda")
     cb = dev(synth.e2m1_codebook())
     outcb = torch.empty(n, dtype=torch.bfloat16, device="cuda")
-    outputs = [out16, outbf, yv, ym, qp, qa, ys, outcb]
+    b1 = torch.empty(n, dtype=torch.float16, device="cuda")            # one launch for two tensors
+    b2 = torch.empty(5000, dtype=torch.float16, device="cuda")
+    outputs = [out16, outbf, yv, ym, qp, qa, ys, outcb, b1, b2]
 
     def run(stream):
         nf4.nf4_dequantize(d["p"], d["a"], 64, n, out16, stream=stream)
@@ -48,6 +50,8 @@ def test_captured_calls_replay_bit_exactly():
         nf4.nf4_dequant_gemm(d["pm"], d["mq8"], d["ms2"], d["moff"], d["mc2"], 64, N, K, d["x"], B, ys, workspace=ws,
                              stream=stream)
         nf4.nf4_dequantize_dq_codebook(d["p"], d["q8"], d["s2"], d["off"], d["c2"], 256, cb, 64, n, outcb, stream=stream)
+        nf4.nf4_dequantize_batch([dict(packed=d["p"], absmax=d["a"], out=b1, n=n),
+                                  dict(packed=d["p"], absmax=d["a"], out=b2, n=5000)], 64, stream=stream)
 
     side = torch.cuda.Stream()
     run(side)                                              # eager reference (also warms up lazy initialisation)
