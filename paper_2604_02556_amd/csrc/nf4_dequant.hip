@@ -153,7 +153,8 @@ __global__ __launch_bounds__(kWave) void dequant_kernel(const uint8_t* __restric
 
 // Several tensors in one launch: workgroup g belongs to the tensor i with first_group[i] <= g <
 // first_group[i + 1], in the order given, so the write frontier still moves through one tensor after the other.
-// One launch pays the fill and drain of the load -> store pipeline once instead of once per tensor.
+// One launch pays the fill and drain of the load -> store pipeline once instead of once per tensor, which matters
+// for tensors of a few MB (a kernel that lasts a single generation of waves) and not for large ones.
 struct BatchArgs {
     const uint8_t* packed[NF4_BATCH_MAX];
     const float* absmax[NF4_BATCH_MAX];
