@@ -21,21 +21,19 @@
 // through a per-wave LDS buffer, one 128-bit write and read each, and the block
 // scales come from the lane that loaded them with ds_bpermute.
 // Two register sets alternate, the next window's codes in flight while this
-// one's are expanded.
+// one's are expanded.  The levels come from the byte-indexed pair table
+// (issue_pair_lookups, 64 KiB at LDS address 0), the weight is narrowed to FP16 by
+// one mixed-precision instruction (scaled_pack2_f16).
 //
-// Where the time goes (ablations of this kernel, 8192 x 28672, 16 tokens): the
-// arithmetic alone 27 us, the loads alone 36 us (codes 25 us -- 128 bytes per row
-// and window is a poor pattern for HBM, a plain read of the same bytes takes 19;
-// the scattered 1-byte scale codes and second-level scales +6; activations
-// +1..5), both together 50 us.  They overlap badly: when the memory queues are
-// full a wave blocks in the issue of its next load instead of computing, and
-// with one barrier per window all 16 waves are in that state together.  The
-// arithmetic alone runs at the issue limit of one instruction per 4 cycles and
-// SIMD (4 waves x 8 steps x 32 instructions x 4 cycles = the 4100 cycles a window
-// of it takes).  Requesting two windows ahead, unpredicated loads from uniform
-// bases, loads spread over the arithmetic steps and windows of 512 k instead of
-// 256 were each built and measured: no gain (the 512 form stayed for up to 32
-// tokens: half as many barriers).
+// Where the time goes (8192 x 28672, 16 tokens, 39-42 us for the kernel): the
+// loads alone take about 20 us (a plain read of the same bytes 19), the
+// arithmetic alone about 17 us, and the two add up rather than overlap: when the
+// memory queues are full a wave blocks in the issue of its next load instead of
+// computing, and with one barrier per window all 16 waves are in that state
+// together.  Without the scale loads the kernel would be 3 us faster.  Requesting
+// two windows ahead, loads spread over the arithmetic steps, waves of a SIMD in
+// opposite phases and dedicated loader waves that bring the data straight into
+// LDS were each built and measured: no gain.
 //
 // Since all waves of a workgroup share k, K is split across workgroups instead:
 // blockIdx.y = split s takes `wps` consecutive windows and writes its partial
