@@ -166,12 +166,12 @@ def main():
         torch.cuda.synchronize()
         b.copy_(a)                                      # reads 268435456 bytes, writes 268435456 bytes
         torch.cuda.synchronize()
-    result["per_shape"] = per_shape(torch, nf4, stream, tensors, names, out)
-    result["stream_one_launch_per_layer"] = batched_stream(torch, nf4, stream, tensors, names, layers,
-                                                           bytes_per_step)
-    result["sum_of_kernel_times_ms_per_step"] = round(sum(v["us"] for v in result["per_shape"].values())
-                                                      * layers / 1e3, 4)
-    if not args.no_extra:
+    if not args.no_extra:                              # --no-extra: the timed stream only (what profiles/ traces)
+        result["per_shape"] = per_shape(torch, nf4, stream, tensors, names, out)
+        result["stream_one_launch_per_layer"] = batched_stream(torch, nf4, stream, tensors, names, layers,
+                                                               bytes_per_step)
+        result["sum_of_kernel_times_ms_per_step"] = round(sum(v["us"] for v in result["per_shape"].values())
+                                                          * layers / 1e3, 4)
         legs = {"dq": ("dq_bf16_gemma27b", leg_dq), "gemv": ("gemv_70b_mlp", leg_gemv),
                 "quantize": ("quantize_70b_gate", leg_quantize), "layer": ("layer_replay_qwen3_32b", leg_layer_replay),
                 "formats": ("block_sizes_and_codebooks_8192x28672", leg_formats)}
