@@ -117,3 +117,38 @@ def test_random_gemv_and_gemm_cases():
             rms = np.sqrt(np.mean(ref ** 2)) + 1e-30
             ok = np.abs(yh - ref) <= 1e-2 * np.abs(ref) + 1e-2 * rms
             assert ok.all(), f"case {case}: N={N} K={K} bs={bs} B={B} {fn.__name__}"
+
+
+def test_random_long_rows_gemv_and_both_gemm_algorithms():
+    """Rows around and beyond 16384 elements (where the GEMV changes kernels), lengths that are not multiples of
+    the 256- or 512-wide windows of the split GEMM, row counts that do not fill the last workgroup."""
+    rng = np.random.Generator(np.random.PCG64(2027))
+    lengths = [16384 - 64, 16384, 16384 + 64, 16384 + 2048 + 320, 20480, 24576 + 192, 28672, 32768 + 128]
+    for case, K in enumerate(lengths):
+        N = int(rng.integers(1, 300))
+        w = synth.gaussian_weights(N * K, 0.015, seed=60_000 + case)
+        p, a = oracle.quantize(w)
+        q8, s2, off, c2 = oracle.dq_encode(a)
+        dp, dq8, ds2, doff, dc2 = dev(p), dev(q8), dev(s2), dev(off), dev(c2)
+        rows = np.unique(np.concatenate([[0, N - 1], rng.integers(0, N, 6)]))      # oracle on sampled rows
+        for B, which in ((int(rng.integers(1, 7)), "gemv"), (int(rng.integers(7, 17)), "gemv"),
+                         (int(rng.integers(1, 65)), "gemm"), (int(rng.integers(1, 65)), "gemm split")):
+            x = synth.activations_fp16(B, K, seed=70_000 + case)
+            y = torch.full((B, N), float("nan"), dtype=torch.float16, device="cuda")
+            if which == "gemv":
+                nf4.nf4_dequant_gemv(dp, dq8, ds2, doff, dc2, 64, N, K, dev(x), B, y)
+                ofn = oracle.dequant_gemv_rows
+            else:
+                ws = None
+                if which == "gemm split":
+                    ws = torch.empty(nf4.nf4_dequant_gemm_workspace_bytes(N, K, B), dtype=torch.uint8, device="cuda")
+                nf4.nf4_dequant_gemm(dp, dq8, ds2, doff, dc2, 64, N, K, dev(x), B, y, workspace=ws)
+                ofn = oracle.dequant_gemm_rows
+            torch.cuda.synchronize()
+            yh = y.cpu().numpy().astype(np.float64)
+            assert np.isfinite(yh).all(), f"K={K} N={N} B={B} {which}"
+            for r in rows:
+                _, ref = ofn(p, q8, s2, off, c2, N, K, x.view(np.uint16), int(r), 1)
+                rms = np.sqrt(np.mean(yh ** 2)) + 1e-30
+                ok = np.abs(yh[:, r:r + 1] - ref) <= 1e-2 * np.abs(ref) + 1e-2 * rms
+                assert ok.all(), f"K={K} N={N} B={B} {which} row {r}"
