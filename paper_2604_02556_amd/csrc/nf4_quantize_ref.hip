@@ -69,25 +69,86 @@ __global__ __launch_bounds__(kQThreads) void quantize_kernel(const float* __rest
     }
 }
 
-// offset = float(sum(absmax) / nb), the sum taken in double in index order by
-// one lane, so that it equals a sequential CPU sum bit for bit.  The wave only
-// helps by staging 1024 values at a time in LDS.
-__global__ __launch_bounds__(kWave) void dq_offset_kernel(const float* __restrict__ absmax, int64_t nb,
-                                                          float* __restrict__ offset,
-                                                          float* __restrict__ code2) {
+// offset = float(sum(absmax) / nb) with the sum as a sequential double-precision sum in index order would give
+// it, bit for bit.  Taken literally that is one lane adding 3.7 million values (56 ms for a 8192 x 28672
+// tensor).  But a double holds 53 bits: when every partial sum -- of any subset, in any order -- is exactly
+// representable, all summation orders give the same, exact, result.  With non-negative terms that is the case
+// if the total is below 2^53 units in the last place of the smallest non-zero term, i.e. total < 2^(e_min + 30)
+// for a smallest term 1.m x 2^e_min (FP32 subnormals: e_min = -126).  So 1024 threads add strided slices,
+// a tree combines them, and only if the test fails (scales spread over more than about 2^29, or a non-finite
+// or negative value) does one lane redo the sum in index order.
+constexpr int kOffsetThreads = 1024;
+
+__global__ __launch_bounds__(kOffsetThreads) void dq_offset_kernel(const float* __restrict__ absmax, int64_t nb,
+                                                                   float* __restrict__ offset,
+                                                                   float* __restrict__ code2) {
+    __shared__ double part[kOffsetThreads];
+    __shared__ int emin_part[kOffsetThreads];
     __shared__ float buf[1024];
-    for (int u = threadIdx.x; u < 256; u += kWave) code2[u] = (float)(u - 127) / 127.0f;
+    __shared__ int exact;
+    const int tid = threadIdx.x;
+    for (int u = tid; u < 256; u += kOffsetThreads) code2[u] = (float)(u - 127) / 127.0f;
+
+    double acc = 0.0;
+    int emin = 1 << 20;                                    // biased exponent of the smallest non-zero term
+    bool clean = true;                                     // all terms finite and non-negative
+    auto take = [&](float v) {
+        const uint32_t bits = __float_as_uint(v);
+        const int e = (int)((bits >> 23) & 0xFF);
+        clean = clean && (bits >> 31) == 0 && e != 0xFF;
+        if ((bits & 0x7FFFFFFFu) != 0) {
+            const int eff = e == 0 ? 1 : e;                // subnormals share the exponent of the smallest normals
+            emin = eff < emin ? eff : emin;
+        }
+        acc += (double)v;
+    };
+    constexpr int kAhead = 8;                              // loads in flight per thread (the order of an exact sum is free)
+    int64_t i = tid;
+    for (; i + (kAhead - 1) * kOffsetThreads < nb; i += kAhead * kOffsetThreads) {
+        float v[kAhead];
+#pragma unroll
+        for (int j = 0; j < kAhead; ++j) v[j] = absmax[i + j * kOffsetThreads];
+#pragma unroll
+        for (int j = 0; j < kAhead; ++j) take(v[j]);
+    }
+    for (; i < nb; i += kOffsetThreads) take(absmax[i]);
+    part[tid] = acc;
+    emin_part[tid] = clean ? emin : -1;                    // -1 poisons the minimum
+    __syncthreads();
+    for (int half = kOffsetThreads / 2; half >= 1; half >>= 1) {
+        if (tid < half) {
+            part[tid] += part[tid + half];
+            const int o = emin_part[tid + half];
+            emin_part[tid] = o < emin_part[tid] ? o : emin_part[tid];
+        }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        const double total = part[0];
+        const int e = emin_part[0];
+        bool ok = e >= 0;                                  // no negative or non-finite term
+        if (ok && e != (1 << 20)) {                        // some non-zero term: total < 2^(e_min + 30)
+            const double limit = __builtin_ldexp(1.0, (e - 127) + 30);
+            ok = total < limit;
+        }
+        exact = ok ? 1 : 0;
+        if (ok) offset[0] = (float)(total / (double)nb);
+    }
+    __syncthreads();
+    if (exact) return;
+
+    // the literal definition: index order, one lane; the block only stages 1024 values at a time in LDS
     double sum = 0.0;
     for (int64_t base = 0; base < nb; base += 1024) {
         const int64_t left = nb - base;
         const int cnt = left < 1024 ? (int)left : 1024;
         __syncthreads();
-        for (int j = threadIdx.x; j < cnt; j += kWave) buf[j] = absmax[base + j];
+        if (tid < cnt) buf[tid] = absmax[base + tid];
         __syncthreads();
-        if (threadIdx.x == 0)
+        if (tid == 0)
             for (int j = 0; j < cnt; ++j) sum += (double)buf[j];
     }
-    if (threadIdx.x == 0) offset[0] = (float)(sum / (double)nb);
+    if (tid == 0) offset[0] = (float)(sum / (double)nb);
 }
 
 // One wave per group of `group` first-level scales (256 in the format's default).
@@ -160,7 +221,7 @@ extern "C" int nf4_quantize_ref_codebook(const float* src, int64_t n, int blocks
     if (rc != NF4_OK || !dq) return rc;
 
     const int64_t ng = (nb + dq_group - 1) / dq_group;
-    hipLaunchKernelGGL(dq_offset_kernel, dim3(1), dim3(kWave), 0, s, (const float*)absmax, nb, offset, code2);
+    hipLaunchKernelGGL(dq_offset_kernel, dim3(1), dim3(kOffsetThreads), 0, s, (const float*)absmax, nb, offset, code2);
     rc = record_hip(hipGetLastError());
     if (rc != NF4_OK) return rc;
     int64_t g2 = (ng + kQWaves - 1) / kQWaves;

@@ -59,3 +59,37 @@ def test_double_quant_outputs_match(n):
     assert g["offset"][0] == off[0]
     assert np.array_equal(g["scale2"][:s2.size], s2)
     assert np.array_equal(g["absmax_q8"][:q8.size], q8)
+
+
+@pytest.mark.parametrize("kind", ["wide", "tiny_and_huge", "subnormal", "zeros", "inexact_sum"])
+def test_mean_offset_equals_the_sequential_double_sum_for_any_spread_of_scales(kind):
+    """The offset is float(sum / nb) with the sum a double-precision sum in index order.  The kernel adds in
+    parallel when it can prove that every order gives the same (exact) sum, and in index order otherwise; either
+    way the bits must be the oracle's.  Scales that span few binades (exact), span 2^100 (inexact: the order
+    matters), are subnormal, are all zero, or are chosen so that rounding in the sum really happens."""
+    rng = np.random.Generator(np.random.PCG64(11))
+    nb = 256 * 37 + 19
+    if kind == "wide":
+        mag = np.exp2(rng.uniform(-60, 40, nb)).astype(np.float32)
+    elif kind == "tiny_and_huge":
+        mag = np.where(rng.random(nb) < 0.5, np.float32(1e-30), np.float32(3e8)).astype(np.float32)
+        mag *= rng.uniform(1, 2, nb).astype(np.float32)
+    elif kind == "subnormal":
+        mag = (rng.integers(1, 1 << 20, nb).astype(np.uint32)).view(np.float32)      # subnormal FP32 values
+    elif kind == "zeros":
+        mag = np.zeros(nb, np.float32)
+    else:                                               # 2^30 next to values with all 24 bits set around 1
+        mag = rng.uniform(0.5, 2.0, nb).astype(np.float32)
+        mag[::97] = np.float32(2.0 ** 31)
+    w = np.zeros(nb * 64, np.float32)
+    w[::64] = mag * rng.choice([-1.0, 1.0], nb).astype(np.float32)                   # block i has absmax mag[i]
+    p, a = oracle.quantize(w)
+    assert np.array_equal(a, mag)
+    q8, s2, off, c2 = oracle.dq_encode(a)
+    # the oracle's offset is the plain sequential sum (pinned here against numpy's own sequential accumulate)
+    seq = np.float32(np.add.accumulate(mag.astype(np.float64))[-1] / nb) if nb else np.float32(0)
+    assert off[0] == seq
+    g = quantize_gpu(w, dq=True)
+    assert g["offset"].view(np.uint32)[0] == off.view(np.uint32)[0]
+    assert np.array_equal(g["scale2"][:s2.size].view(np.uint32), s2.view(np.uint32))
+    assert np.array_equal(g["absmax_q8"][:q8.size], q8)
