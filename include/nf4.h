@@ -212,6 +212,19 @@ int nf4_quantize_ref_codebook(const float* src, int64_t n, int blocksize, const 
 int nf4_quantize(const float* src, int64_t n, int blocksize, uint8_t* packed, float* absmax,
                  void* stream);
 
+/*
+ * The second level alone: double-quantises an existing array of nb block scales
+ * (e.g. nf4_quantize's absmax) exactly as nf4_quantize_ref_codebook does, bit for
+ * bit: code2[u] = (u - 127)/127, offset = mean(absmax) (the double-precision sum
+ * in index order), scale2[g] = max |absmax - offset| over each group of dq_group
+ * blocks (a power of two in [1, 65536], else NF4_ERR_SHAPE), absmax_q8 = 127 +
+ * clamp(rint(127 * (absmax - offset) / scale2), -127, 127).  Writes
+ * absmax_q8[nb], scale2[ceil(nb / dq_group)], offset[1], code2[256]; absmax is
+ * only read.
+ */
+int nf4_dq_encode(const float* absmax, int64_t nb, int dq_group, uint8_t* absmax_q8, float* scale2,
+                  float* offset, float* code2, void* stream);
+
 /* hipError_t (as int) behind the most recent NF4_ERR_HIP on the calling thread; 0 if none. */
 int nf4_last_hip_error(void);
 

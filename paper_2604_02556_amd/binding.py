@@ -59,6 +59,7 @@ def lib():
     for f in (L.nf4_dequantize_codebook, L.nf4_dequantize_dq_codebook, L.nf4_quantize_ref_codebook):
         f.restype = i32
     L.nf4_quantize.argtypes = [vp, i64, i32, vp, vp, vp]
+    L.nf4_dq_encode.argtypes = [vp, i64, i32, vp, vp, vp, vp, vp]
     for f in (L.nf4_dequantize, L.nf4_dequantize_dq, L.nf4_dequant_gemv, L.nf4_quantize_ref, L.nf4_quantize,
               L.nf4_last_hip_error):
         f.restype = i32
@@ -174,6 +175,11 @@ def nf4_quantize_ref(src, n, blocksize, packed, absmax, absmax_q8=None, scale2=N
                      code2=None, stream=None):
     _check(lib().nf4_quantize_ref(_ptr(src), n, blocksize, _ptr(packed), _ptr(absmax), _ptr(absmax_q8),
                                   _ptr(scale2), _ptr(offset), _ptr(code2), _stream(stream)))
+
+
+def nf4_dq_encode(absmax, nb, dq_group, absmax_q8, scale2, offset, code2, stream=None):
+    _check(lib().nf4_dq_encode(_ptr(absmax), nb, dq_group, _ptr(absmax_q8), _ptr(scale2), _ptr(offset), _ptr(code2),
+                               _stream(stream)))
 
 
 def nf4_quantize(src, n, blocksize, packed, absmax, stream=None):

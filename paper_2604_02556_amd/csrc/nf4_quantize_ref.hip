@@ -216,17 +216,29 @@ extern "C" int nf4_quantize_ref_codebook(const float* src, int64_t n, int blocks
 
     hipStream_t s = (hipStream_t)stream;
     const int64_t nb = (n + blocksize - 1) / blocksize;
-    const int64_t cap = (int64_t)compute_units() * 16;
     int rc = launch_quantize_ref_range(src, n, blocksize, codebook, packed, absmax, s);
     if (rc != NF4_OK || !dq) return rc;
 
+    return nf4_dq_encode(absmax, nb, dq_group, absmax_q8, scale2, offset, code2, stream);
+}
+
+extern "C" int nf4_dq_encode(const float* absmax, int64_t nb, int dq_group, uint8_t* absmax_q8, float* scale2,
+                             float* offset, float* code2, void* stream) {
+    using namespace nf4;
+    if (nb < 0) return NF4_ERR_SIZE;
+    if (log2_dq_group(dq_group) < 0) return NF4_ERR_SHAPE;
+    if (nb == 0) return NF4_OK;
+    if (!absmax || !absmax_q8 || !scale2 || !offset || !code2) return NF4_ERR_NULL;
+    if (!aligned(absmax, 4) || !aligned(scale2, 4) || !aligned(offset, 4) || !aligned(code2, 4)) return NF4_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)stream;
+    const int64_t cap = (int64_t)compute_units() * 16;
     const int64_t ng = (nb + dq_group - 1) / dq_group;
-    hipLaunchKernelGGL(dq_offset_kernel, dim3(1), dim3(kOffsetThreads), 0, s, (const float*)absmax, nb, offset, code2);
-    rc = record_hip(hipGetLastError());
+    hipLaunchKernelGGL(dq_offset_kernel, dim3(1), dim3(kOffsetThreads), 0, s, absmax, nb, offset, code2);
+    int rc = record_hip(hipGetLastError());
     if (rc != NF4_OK) return rc;
     int64_t g2 = (ng + kQWaves - 1) / kQWaves;
     g2 = g2 < cap ? g2 : cap;
-    hipLaunchKernelGGL(dq_encode_kernel, dim3((unsigned)g2), dim3(kQThreads), 0, s, (const float*)absmax, nb, ng,
+    hipLaunchKernelGGL(dq_encode_kernel, dim3((unsigned)g2), dim3(kQThreads), 0, s, absmax, nb, ng,
                        (int64_t)dq_group, (const float*)offset, absmax_q8, scale2);
     return record_hip(hipGetLastError());
 }

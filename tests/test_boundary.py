@@ -30,7 +30,7 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(L):
     names = declared_functions()
     assert set(names) >= {"nf4_dequantize", "nf4_dequantize_dq", "nf4_dequant_gemv", "nf4_quantize_ref",
-                          "nf4_quantize", "nf4_dequant_gemm", "nf4_dequant_gemm_workspace_bytes", "nf4_dequantize_batch", "nf4_dequantize_codebook",
+                          "nf4_quantize", "nf4_dq_encode", "nf4_dequant_gemm", "nf4_dequant_gemm_workspace_bytes", "nf4_dequantize_batch", "nf4_dequantize_codebook",
                           "nf4_dequantize_dq_codebook", "nf4_quantize_ref_codebook", "nf4_last_hip_error", "nf4_status_string"}
     for name in names:
         assert hasattr(L, name), name
@@ -153,6 +153,19 @@ def test_quantize_ref_argument_checks(L):
     assert f(P, 5, 64, P, None, None, None, None, None, None) == E_NULL
     assert f(P, 5, 64, P, P, P, None, P, P, None) == E_NULL             # DQ wants all four outputs
     assert f(P + 2, 5, 64, P, P, None, None, None, None, None) == E_ALIGN
+
+
+def test_dq_encode_argument_checks(L):
+    f = L.nf4_dq_encode
+    assert f(P, -1, 256, P, P, P, P, None) == E_SIZE
+    assert f(P, 10, 100, P, P, P, P, None) == E_SHAPE
+    assert f(P, 10, 0, P, P, P, P, None) == E_SHAPE
+    assert f(None, 0, 256, None, None, None, None, None) == OK
+    assert f(None, 10, 256, P, P, P, P, None) == E_NULL
+    assert f(P, 10, 256, None, P, P, P, None) == E_NULL
+    assert f(P, 10, 256, P, P, None, P, None) == E_NULL
+    assert f(P + 2, 10, 256, P, P, P, P, None) == E_ALIGN
+    assert f(P, 10, 256, P + 1, P + 2, P, P, None) == E_ALIGN           # absmax_q8 is bytes; scale2 is not
 
 
 def test_codebook_entry_points_argument_checks(L):

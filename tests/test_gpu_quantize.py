@@ -145,3 +145,25 @@ def test_other_block_sizes_match_the_oracle(blocksize, n):
     gp, ga = quantize_gpu(w, blocksize)
     assert np.array_equal(ga.view(np.uint32), a.view(np.uint32))
     assert np.array_equal(gp, p)
+
+
+@pytest.mark.parametrize("group", [256, 64, 1])
+@pytest.mark.parametrize("n", [64 * 256 * 5 + 64 * 7, 1_000_003])
+def test_tuned_quantiser_followed_by_the_second_level_equals_the_oracle(n, group):
+    """nf4_quantize + nf4_dq_encode: the tuned first level and the second level as separate calls give the
+    oracle's codes, scale codes, second-level scales, offset and map bit for bit."""
+    w = synth.gaussian_weights(n, 0.02, seed=n % 977)
+    p, a = oracle.quantize(w)
+    q8, s2, off, c2 = oracle.dq_encode_group(a, group)
+    bufs = nf4.alloc_quantized(n, 64, dq=True, dq_group=group)
+    for t in bufs.values():
+        t.view(torch.uint8).fill_(0xCD)
+    nf4.nf4_quantize(dev(w), n, 64, bufs["packed"], bufs["absmax"])
+    nf4.nf4_dq_encode(bufs["absmax"], a.size, group, bufs["absmax_q8"], bufs["scale2"], bufs["offset"], bufs["code2"])
+    torch.cuda.synchronize()
+    g = {k: v.cpu().numpy() for k, v in bufs.items()}
+    assert np.array_equal(g["packed"][:p.size], p) and np.array_equal(g["absmax"][:a.size], a)
+    assert np.array_equal(g["absmax_q8"][:q8.size], q8)
+    assert np.array_equal(g["scale2"][:s2.size].view(np.uint32), s2.view(np.uint32))
+    assert g["offset"].view(np.uint32)[0] == off.view(np.uint32)[0]
+    assert np.array_equal(g["code2"].view(np.uint32), c2.view(np.uint32))
