@@ -404,9 +404,13 @@ def leg_quantize(torch, nf4, synth, stream, gen, src):
     us = time_on_stream(torch, stream, lambda: nf4.nf4_quantize(w, n, 64, b["packed"], b["absmax"], stream=stream), 20)
     us_ref = time_on_stream(torch, stream,
                             lambda: nf4.nf4_quantize_ref(w, n, 64, b["packed"], b["absmax"], stream=stream), 5)
+    d = nf4.alloc_quantized(n, 64, dq=True, device=src.device)      # the second level on the tuned quantiser's scales
+    us_dq = time_on_stream(torch, stream, lambda: nf4.nf4_dq_encode(b["absmax"], n // 64, 256, d["absmax_q8"],
+                                                                     d["scale2"], d["offset"], d["code2"],
+                                                                     stream=stream), 20)
     res = {"elements": n, "us": round(us, 2), "GB/s": round(bytes_ / (us * 1e-6) / 1e9, 1),
            "frac_of_hbm_peak": round(bytes_ / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
-           "reference_quantizer_us": round(us_ref, 2), "other_block_sizes": {}}
+           "reference_quantizer_us": round(us_ref, 2), "dq_encode_us": round(us_dq, 2), "other_block_sizes": {}}
     for bs in (128, 512, 2048):
         bb = nf4.alloc_quantized(n, bs, device=src.device)
         t = time_on_stream(torch, stream, lambda: nf4.nf4_quantize(w, n, bs, bb["packed"], bb["absmax"], stream=stream), 10)

@@ -77,22 +77,26 @@ __global__ __launch_bounds__(kQThreads) void quantize_kernel(const float* __rest
 // for a smallest term 1.m x 2^e_min (FP32 subnormals: e_min = -126).  So 1024 threads add strided slices,
 // a tree combines them, and only if the test fails (scales spread over more than about 2^29, or a non-finite
 // or negative value) does one lane redo the sum in index order.
+// Large arrays are first summed slice by slice by many workgroups (dq_partial_kernel) into a scratch area -- the
+// head of the absmax_q8 output, which is written only afterwards -- and dq_offset_kernel then combines the slices.
 constexpr int kOffsetThreads = 1024;
+constexpr int kPartialThreads = 256;
+constexpr int kMaxPartials = 1024;                         // slices at most (16 bytes of scratch each)
+constexpr int kNoTerm = 1 << 20;                           // "no non-zero term seen"
 
-__global__ __launch_bounds__(kOffsetThreads) void dq_offset_kernel(const float* __restrict__ absmax, int64_t nb,
-                                                                   float* __restrict__ offset,
-                                                                   float* __restrict__ code2) {
-    __shared__ double part[kOffsetThreads];
-    __shared__ int emin_part[kOffsetThreads];
-    __shared__ float buf[1024];
-    __shared__ int exact;
-    const int tid = threadIdx.x;
-    for (int u = tid; u < 256; u += kOffsetThreads) code2[u] = (float)(u - 127) / 127.0f;
+struct SlicePartial {
+    double sum;
+    int emin;                                              // smallest biased exponent; kNoTerm; or -1: not clean
+    int pad;
+};
 
+// Running state of one thread: sum, smallest exponent of a non-zero term, and whether all terms were finite and
+// non-negative.
+struct OffsetAcc {
     double acc = 0.0;
-    int emin = 1 << 20;                                    // biased exponent of the smallest non-zero term
-    bool clean = true;                                     // all terms finite and non-negative
-    auto take = [&](float v) {
+    int emin = kNoTerm;
+    bool clean = true;
+    __device__ __forceinline__ void take(float v) {
         const uint32_t bits = __float_as_uint(v);
         const int e = (int)((bits >> 23) & 0xFF);
         clean = clean && (bits >> 31) == 0 && e != 0xFF;
@@ -101,17 +105,72 @@ __global__ __launch_bounds__(kOffsetThreads) void dq_offset_kernel(const float* 
             emin = eff < emin ? eff : emin;
         }
         acc += (double)v;
-    };
-    constexpr int kAhead = 8;                              // loads in flight per thread (the order of an exact sum is free)
-    int64_t i = tid;
-    for (; i + (kAhead - 1) * kOffsetThreads < nb; i += kAhead * kOffsetThreads) {
-        float v[kAhead];
-#pragma unroll
-        for (int j = 0; j < kAhead; ++j) v[j] = absmax[i + j * kOffsetThreads];
-#pragma unroll
-        for (int j = 0; j < kAhead; ++j) take(v[j]);
     }
-    for (; i < nb; i += kOffsetThreads) take(absmax[i]);
+    // elements first + tid, first + tid + stride, ... below `end`, eight loads in flight (the order of an exact
+    // sum is free)
+    __device__ __forceinline__ void take_strided(const float* __restrict__ a, int64_t first, int64_t end, int tid,
+                                                 int stride) {
+        constexpr int kAhead = 8;
+        int64_t i = first + tid;
+        for (; i + (int64_t)(kAhead - 1) * stride < end; i += (int64_t)kAhead * stride) {
+            float v[kAhead];
+#pragma unroll
+            for (int j = 0; j < kAhead; ++j) v[j] = a[i + (int64_t)j * stride];
+#pragma unroll
+            for (int j = 0; j < kAhead; ++j) take(v[j]);
+        }
+        for (; i < end; i += stride) take(a[i]);
+    }
+};
+
+__global__ __launch_bounds__(kPartialThreads) void dq_partial_kernel(const float* __restrict__ absmax, int64_t nb,
+                                                                      int64_t per_slice,
+                                                                      SlicePartial* __restrict__ partials) {
+    __shared__ double part[kPartialThreads];
+    __shared__ int emin_part[kPartialThreads];
+    const int tid = threadIdx.x;
+    const int64_t first = (int64_t)blockIdx.x * per_slice;
+    const int64_t end = first + per_slice < nb ? first + per_slice : nb;
+    OffsetAcc st;
+    st.take_strided(absmax, first, end, tid, kPartialThreads);
+    part[tid] = st.acc;
+    emin_part[tid] = st.clean ? st.emin : -1;
+    __syncthreads();
+    for (int half = kPartialThreads / 2; half >= 1; half >>= 1) {
+        if (tid < half) {
+            part[tid] += part[tid + half];
+            const int o = emin_part[tid + half];
+            emin_part[tid] = o < emin_part[tid] ? o : emin_part[tid];
+        }
+        __syncthreads();
+    }
+    if (tid == 0) partials[blockIdx.x] = SlicePartial{part[0], emin_part[0], 0};
+}
+
+__global__ __launch_bounds__(kOffsetThreads) void dq_offset_kernel(const float* __restrict__ absmax, int64_t nb,
+                                                                   const SlicePartial* __restrict__ partials,
+                                                                   int slices, float* __restrict__ offset,
+                                                                   float* __restrict__ code2) {
+    __shared__ double part[kOffsetThreads];
+    __shared__ int emin_part[kOffsetThreads];
+    __shared__ float buf[1024];
+    __shared__ int exact;
+    const int tid = threadIdx.x;
+    for (int u = tid; u < 256; u += kOffsetThreads) code2[u] = (float)(u - 127) / 127.0f;
+
+    OffsetAcc st;
+    if (slices > 0) {                                      // the slices' sums are the terms (slices <= kOffsetThreads)
+        if (tid < slices) {
+            st.acc = partials[tid].sum;
+            st.emin = partials[tid].emin;
+            st.clean = st.emin >= 0;
+        }
+    } else {
+        st.take_strided(absmax, 0, nb, tid, kOffsetThreads);
+    }
+    double acc = st.acc;
+    int emin = st.emin;
+    bool clean = st.clean;
     part[tid] = acc;
     emin_part[tid] = clean ? emin : -1;                    // -1 poisons the minimum
     __syncthreads();
@@ -127,7 +186,7 @@ __global__ __launch_bounds__(kOffsetThreads) void dq_offset_kernel(const float* 
         const double total = part[0];
         const int e = emin_part[0];
         bool ok = e >= 0;                                  // no negative or non-finite term
-        if (ok && e != (1 << 20)) {                        // some non-zero term: total < 2^(e_min + 30)
+        if (ok && e != kNoTerm) {                        // some non-zero term: total < 2^(e_min + 30)
             const double limit = __builtin_ldexp(1.0, (e - 127) + 30);
             ok = total < limit;
         }
@@ -233,8 +292,27 @@ extern "C" int nf4_dq_encode(const float* absmax, int64_t nb, int dq_group, uint
     hipStream_t s = (hipStream_t)stream;
     const int64_t cap = (int64_t)compute_units() * 16;
     const int64_t ng = (nb + dq_group - 1) / dq_group;
-    hipLaunchKernelGGL(dq_offset_kernel, dim3(1), dim3(kOffsetThreads), 0, s, absmax, nb, offset, code2);
-    int rc = record_hip(hipGetLastError());
+    // slices of at least 16384 scales, as many as fit the scratch area at the (8-byte aligned) head of absmax_q8
+    const uintptr_t q8_addr = (uintptr_t)absmax_q8;
+    SlicePartial* partials = (SlicePartial*)((q8_addr + 7) & ~(uintptr_t)7);
+    const int64_t room = (nb - (int64_t)((uintptr_t)partials - q8_addr)) / (int64_t)sizeof(SlicePartial);
+    int64_t slices = nb / 16384;
+    slices = slices < room ? slices : room;
+    slices = slices < kMaxPartials ? slices : kMaxPartials;
+    int rc;
+    if (slices >= 2) {
+        const int64_t per_slice = (nb + slices - 1) / slices;
+        slices = (nb + per_slice - 1) / per_slice;
+        hipLaunchKernelGGL(dq_partial_kernel, dim3((unsigned)slices), dim3(kPartialThreads), 0, s, absmax, nb, per_slice,
+                           partials);
+        rc = record_hip(hipGetLastError());
+        if (rc != NF4_OK) return rc;
+    } else {
+        slices = 0;
+    }
+    hipLaunchKernelGGL(dq_offset_kernel, dim3(1), dim3(kOffsetThreads), 0, s, absmax, nb,
+                       (const SlicePartial*)partials, (int)slices, offset, code2);
+    rc = record_hip(hipGetLastError());
     if (rc != NF4_OK) return rc;
     int64_t g2 = (ng + kQWaves - 1) / kQWaves;
     g2 = g2 < cap ? g2 : cap;

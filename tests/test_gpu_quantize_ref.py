@@ -61,15 +61,17 @@ def test_double_quant_outputs_match(n):
     assert np.array_equal(g["absmax_q8"][:q8.size], q8)
 
 
-@pytest.mark.parametrize("kind", ["wide", "tiny_and_huge", "subnormal", "zeros", "inexact_sum"])
-def test_mean_offset_equals_the_sequential_double_sum_for_any_spread_of_scales(kind):
+@pytest.mark.parametrize("nb", [256 * 37 + 19, 70_001])      # one workgroup / slices summed by many workgroups
+@pytest.mark.parametrize("kind", ["narrow", "wide", "tiny_and_huge", "subnormal", "zeros", "inexact_sum"])
+def test_mean_offset_equals_the_sequential_double_sum_for_any_spread_of_scales(kind, nb):
     """The offset is float(sum / nb) with the sum a double-precision sum in index order.  The kernel adds in
     parallel when it can prove that every order gives the same (exact) sum, and in index order otherwise; either
     way the bits must be the oracle's.  Scales that span few binades (exact), span 2^100 (inexact: the order
     matters), are subnormal, are all zero, or are chosen so that rounding in the sum really happens."""
     rng = np.random.Generator(np.random.PCG64(11))
-    nb = 256 * 37 + 19
-    if kind == "wide":
+    if kind == "narrow":                                # the usual case: every order of summation is exact
+        mag = rng.uniform(0.03, 0.09, nb).astype(np.float32)
+    elif kind == "wide":
         mag = np.exp2(rng.uniform(-60, 40, nb)).astype(np.float32)
     elif kind == "tiny_and_huge":
         mag = np.where(rng.random(nb) < 0.5, np.float32(1e-30), np.float32(3e8)).astype(np.float32)
