@@ -93,21 +93,18 @@ __device__ __forceinline__ void dequant_group(const uint8_t* __restrict__ packed
         // Scales.  Lane l's k-th store covers elements e0 + 512 k + 8 l .. + 7,
         // all inside one quantisation block (blocksize >= 64).
         float s[4];
-        if constexpr (DQ) {
-            // lanes 0..(blocks per tile - 1) each rebuild one block scale; the
-            // others fetch it across lanes afterwards
+        {
+            // lanes 0..(blocks per tile - 1) each fetch (FP32 absmax) or rebuild (double quantisation) one block
+            // scale with a single contiguous load; the others take it across lanes afterwards
             const int per_tile = log2_bs >= 11 ? 1 : (kTileElems >> log2_bs);
             const int64_t b0 = e0 >> log2_bs;
             float mine = 0.0f;
-            if (lane < per_tile) mine = dq_scale(sa, offset, b0 + lane);
+            if (lane < per_tile) mine = DQ ? dq_scale(sa, offset, b0 + lane) : sa.absmax[b0 + lane];
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const int src = log2_bs >= 11 ? 0 : ((512 * k + 8 * lane) >> log2_bs);
                 s[k] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(src << 2, __builtin_bit_cast(int, mine)));
             }
-        } else {
-#pragma unroll
-            for (int k = 0; k < 4; ++k) s[k] = sa.absmax[(e0 + 512 * k + 8 * lane) >> log2_bs];
         }
 
         *(u32x4*)&stage[lane * 4] = codes;
