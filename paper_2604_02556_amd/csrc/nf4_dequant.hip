@@ -12,6 +12,11 @@
 //     the 16 bytes at 16*l): four such stores per tile, each covering whole
 //     cache lines.  Letting each lane store the 64 bytes it decoded itself
 //     (16-byte pieces at a 64-byte stride) ran at under half the speed;
+//   * the tile's block scales are fetched with one contiguous load by the
+//     first 32 lanes (block size 64) and handed to the other lanes with
+//     ds_bpermute.  Loading them where they are used -- four loads per lane in
+//     which eight lanes share an address -- moves the same bytes with four
+//     times the requests and cost 2.4 % of the stream's throughput;
 //   * stores carry the non-temporal hint (+6 % measured): the output is
 //     written once and not re-read by this kernel;
 //   * the grid is one-shot -- one single-wave workgroup per tile, dispatched in

@@ -111,8 +111,13 @@ __global__ __launch_bounds__(THREADS) void study_kernel(const uint8_t* __restric
     float s[4] = {0.f, 0.f, 0.f, 0.f};
     if (live) {
         codes = *(const u32x4*)(packed + t * 1024 + lane * 16);
+        // the tile's 32 block scales: one contiguous load by lanes 0..31, then shared across lanes
+        float mine = 0.0f;
+        if (lane < 32) mine = absmax[(e0 >> 6) + lane];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) s[k] = absmax[(e0 + 512 * k + 8 * lane) >> 6];
+        for (int k = 0; k < 4; ++k)
+            s[k] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((8 * k + (lane >> 3)) << 2,
+                                                                            __builtin_bit_cast(int, mine)));
     }
 
     Tables tb = {lut, lut2, gtable, 0};
