@@ -29,11 +29,12 @@
 //     and lanes that pick the same level are served by broadcast, so the
 //     lookup cannot conflict (SQ_LDS_BANK_CONFLICT = 0).  Measured against a
 //     VGPR table read with ds_bpermute_b32, a 256-entry byte-pair LDS table, a
-//     table re-read from memory and a pure select chain: the kernel time of the
-//     first three is equal within 2 % (the path is HBM-bound), the plain LDS
-//     table keeps the LDS pipe busy for about half as many cycles as
-//     ds_bpermute, the byte-pair table conflicts, and the last two halve the
-//     throughput;
+//     table re-read from memory and a pure select chain: the LDS tables are
+//     equal within 0.5 % (the path is HBM-bound), ds_bpermute is 3 % slower
+//     (it keeps the LDS pipe busy for almost twice as many cycles), the
+//     byte-pair table conflicts, and the last two halve the throughput.  The
+//     table is written before the wave issues its loads: the other order
+//     measured 1.2 % slower;
 //   * nibble split is a shift and a mask (Sec. IV-D), the product is one FP32
 //     multiply, two products are narrowed and packed per dword by the packed
 //     round-to-nearest-even converts, eight values per 128-bit store;

@@ -107,19 +107,6 @@ __global__ __launch_bounds__(THREADS) void study_kernel(const uint8_t* __restric
     const bool live = t < tiles;
     const int64_t e0 = t * 2048;
 
-    u32x4 codes = {0, 0, 0, 0};
-    float s[4] = {0.f, 0.f, 0.f, 0.f};
-    if (live) {
-        codes = *(const u32x4*)(packed + t * 1024 + lane * 16);
-        // the tile's 32 block scales: one contiguous load by lanes 0..31, then shared across lanes
-        float mine = 0.0f;
-        if (lane < 32) mine = absmax[(e0 >> 6) + lane];
-#pragma unroll
-        for (int k = 0; k < 4; ++k)
-            s[k] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((8 * k + (lane >> 3)) << 2,
-                                                                            __builtin_bit_cast(int, mine)));
-    }
-
     Tables tb = {lut, lut2, gtable, 0};
     if constexpr (P == BPERMUTE) tb.table_reg = (int)level_literal(lane & 15);
     if constexpr (P == LDS16) {
@@ -137,6 +124,19 @@ __global__ __launch_bounds__(THREADS) void study_kernel(const uint8_t* __restric
             lut2[i] = p;
         }
         __syncthreads();
+    }
+    // the loads come after the table is written, as in the library's kernel (the other order measured 1.2 % slower)
+    u32x4 codes = {0, 0, 0, 0};
+    float s[4] = {0.f, 0.f, 0.f, 0.f};
+    if (live) {
+        codes = *(const u32x4*)(packed + t * 1024 + lane * 16);
+        // the tile's 32 block scales: one contiguous load by lanes 0..31, then shared across lanes
+        float mine = 0.0f;
+        if (lane < 32) mine = absmax[(e0 >> 6) + lane];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            s[k] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((8 * k + (lane >> 3)) << 2,
+                                                                            __builtin_bit_cast(int, mine)));
     }
     if (!live) return;
 
