@@ -25,7 +25,11 @@
 //     read per two weights); the double-quantisation map code2 sits in 1 KiB
 //     of LDS;
 //   * the block scale is applied once per lane chunk (sum of level*x first,
-//     then one multiply-add by the scale), not once per element;
+//     then one multiply-add by the scale), not once per element.  Each lane
+//     loads the scale code and second-level scale of its own chunk; the
+//     long-row kernel, where whole steps allow it, fetches the codes of all four
+//     rows with one 16-bit load per lane and shares the decoded scales through
+//     LDS (two memory requests per step instead of eight: 6 % faster);
 //   * addresses of the level table are taken four at a time: two masked copies
 //     of a code dword hold code*4 in each byte, one bit-field extract each;
 //   * each accumulator is reduced across the wave with six DPP adds.
@@ -170,6 +174,81 @@ __device__ __forceinline__ void compute_step(const StepRegs<B, CH, R>& g, const 
     }
 }
 
+// The block scales of a step through two loads instead of eight (block size 64, whole steps, R = 4 rows of
+// CH = 4 dwords per lane: 32 blocks per row and step).  Lane l fetches the two 8-bit codes of blocks 2 (l % 16)
+// and 2 (l % 16) + 1 of row l / 16 as one 16-bit load -- the wave reads the four rows' 32 bytes each in one request
+// -- and their second-level scale (the two blocks share a group: a group starts at an even block), decodes both
+// and leaves them in this wave's LDS slice, where every lane picks up the scale of its own block of each row.
+// Same arithmetic per scale as the per-lane form (table value times second-level scale, rounded, plus offset).
+template <int B>
+__device__ __forceinline__ void load_step_merged(StepRegs<B, 4, 4>& g, const RowBases<4>& rb, uint32_t blocks_per_row,
+                                                 const _Float16* __restrict__ x, int64_t K, int64_t k0, int lane) {
+    const int64_t kb = k0 >> 6;
+    const uint32_t v = (uint32_t)(lane >> 4) * blocks_per_row + 2u * (uint32_t)(lane & 15);   // blocks past (row 0, kb)
+    g.q8[0] = *(const uint16_t*)(rb.q8[0] + kb + v);
+    const int64_t gb = (int64_t)rb.blk_lo[0] + kb;
+    g.s2[0] = (rb.s2[0] + (gb >> 8))[((uint32_t)(gb & 255) + v) >> 8];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const u32x4 c = __builtin_nontemporal_load((const u32x4*)(rb.codes[r] + (k0 >> 1)) + lane);
+        g.q[r][0] = c[0]; g.q[r][1] = c[1]; g.q[r][2] = c[2]; g.q[r][3] = c[3];
+    }
+#pragma unroll
+    for (int b = 0; b < B; ++b) {
+        const half8_t* xb = (const half8_t*)(x + (int64_t)b * K + k0);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) g.xh[b][c] = xb[lane * 4 + c];
+    }
+}
+
+// Decode the two scales this lane fetched, hand them round through the wave's LDS slice (R x 32 floats) and pick
+// up the scale of this lane's own block of each row.
+__device__ __forceinline__ void merged_scales(uint32_t q8_pair, float s2, const float* code2_lds, float offset,
+                                              float* wave_scales, int lane, float (&sc)[4]) {
+    const float pa = code2_lds[q8_pair & 255u] * s2;               // rounded product, then rounded sum
+    const float pb = code2_lds[q8_pair >> 8] * s2;
+    *(float2_t*)&wave_scales[2 * lane] = (float2_t){pa + offset, pb + offset};   // [row l / 16][block 2 (l % 16)]
+    wave_lds_fence();
+#pragma unroll
+    for (int r = 0; r < 4; ++r) sc[r] = wave_scales[32 * r + (lane >> 1)];       // lane's 32 elements: block lane / 2
+}
+
+// One step of the long-row kernel with the scales fetched that way.
+template <int B>
+__device__ __forceinline__ void compute_step_merged(const StepRegs<B, 4, 4>& g, const uint8_t* table, uint32_t lane_off,
+                                                    const float* code2_lds, float offset, float* wave_scales,
+                                                    int lane, float (&acc)[4][B]) {
+    constexpr int R = 4, CH = 4, U = R * CH;
+    float sc[R];
+    merged_scales(g.q8[0], g.s2[0], code2_lds, offset, wave_scales, lane, sc);
+    float lv[2][8];
+    issue_pair_lookups(g.q[0][0], table, lane_off, lv[0]);
+    float part[B];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {                                  // software pipeline, depth 2
+        const int r = u / CH, c = u % CH;
+        if (u + 1 < U) {
+            issue_pair_lookups(g.q[(u + 1) / CH][(u + 1) % CH], table, lane_off, lv[(u + 1) & 1]);
+            lds_wait<4>();                                         // everything but the 4 just issued has landed
+        } else {
+            lds_wait<0>();
+        }
+        if (c == 0) {
+#pragma unroll
+            for (int b = 0; b < B; ++b) part[b] = 0.0f;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int b = 0; b < B; ++b) part[b] = __builtin_fmaf(lv[u & 1][j], (float)g.xh[b][c][j], part[b]);
+        if (c == CH - 1) {
+#pragma unroll
+            for (int b = 0; b < B; ++b) acc[r][b] = __builtin_fmaf(sc[r], part[b], acc[r][b]);
+        }
+    }
+    wave_lds_fence();                                              // the slice is rewritten by the next step
+}
+
 template <int B, int CH, int R, bool FULL>
 __global__ __launch_bounds__(kWave, 2) void gemv_kernel(const uint8_t* __restrict__ packed,
                                                      const uint8_t* __restrict__ q8,
@@ -278,7 +357,7 @@ __device__ __forceinline__ void compute_step_pair(const StepRegs<B, CH, R>& g, c
     }
 }
 
-template <int B, int CH, int R, bool FULL>
+template <int B, int CH, int R, bool FULL, bool MERGED = false>
 __global__ __launch_bounds__(kPairWaves * kWave) void gemv_pair_kernel(const uint8_t* __restrict__ packed,
                                                                        const uint8_t* __restrict__ q8,
                                                                        const float* __restrict__ scale2,
@@ -291,7 +370,9 @@ __global__ __launch_bounds__(kPairWaves * kWave) void gemv_pair_kernel(const uin
     constexpr int kSlice = E * kWave;
     constexpr int kThreads = kPairWaves * kWave;
     // one LDS object, so that the pair table sits at address 0: table | 16 levels | code2
-    __shared__ __attribute__((aligned(16))) uint8_t smem[kPairTableBytes + 64 + 1024];
+    static_assert(!MERGED || (FULL && CH == 4 && R == 4), "the two-load scale fetch is for whole steps of 4 x 4 dwords");
+    constexpr int kScaleBytes = MERGED ? kPairWaves * R * 32 * 4 : 0;   // per wave: R rows x 32 block scales
+    __shared__ __attribute__((aligned(16))) uint8_t smem[kPairTableBytes + 64 + 1024 + kScaleBytes];
     float* lut = (float*)(smem + kPairTableBytes);
     float* code2_lds = (float*)(smem + kPairTableBytes + 64);
 
@@ -328,14 +409,28 @@ __global__ __launch_bounds__(kPairWaves * kWave) void gemv_pair_kernel(const uin
         rb.s2[r] = scale2 + (row_blk >> 8);
     }
     StepRegs<B, CH, R> ping, pong;
-    load_step<B, CH, R, FULL>(ping, rb, x, log2_bs, K, rows, 0, lane);
-    for (int64_t it = 0;;) {
-        if (it + 1 < steps) load_step<B, CH, R, FULL>(pong, rb, x, log2_bs, K, rows, (it + 1) * kSlice, lane);
-        compute_step_pair<B, CH, R>(ping, smem, lane_off, code2_lds, offset, acc);
-        if (++it >= steps) break;
-        if (it + 1 < steps) load_step<B, CH, R, FULL>(ping, rb, x, log2_bs, K, rows, (it + 1) * kSlice, lane);
-        compute_step_pair<B, CH, R>(pong, smem, lane_off, code2_lds, offset, acc);
-        if (++it >= steps) break;
+    if constexpr (MERGED) {
+        float* wave_scales = (float*)(smem + kPairTableBytes + 64 + 1024) + wave * (R * 32);
+        const uint32_t blocks_per_row = (uint32_t)(K >> 6);
+        load_step_merged<B>(ping, rb, blocks_per_row, x, K, 0, lane);
+        for (int64_t it = 0;;) {
+            if (it + 1 < steps) load_step_merged<B>(pong, rb, blocks_per_row, x, K, (it + 1) * kSlice, lane);
+            compute_step_merged<B>(ping, smem, lane_off, code2_lds, offset, wave_scales, lane, acc);
+            if (++it >= steps) break;
+            if (it + 1 < steps) load_step_merged<B>(ping, rb, blocks_per_row, x, K, (it + 1) * kSlice, lane);
+            compute_step_merged<B>(pong, smem, lane_off, code2_lds, offset, wave_scales, lane, acc);
+            if (++it >= steps) break;
+        }
+    } else {
+        load_step<B, CH, R, FULL>(ping, rb, x, log2_bs, K, rows, 0, lane);
+        for (int64_t it = 0;;) {
+            if (it + 1 < steps) load_step<B, CH, R, FULL>(pong, rb, x, log2_bs, K, rows, (it + 1) * kSlice, lane);
+            compute_step_pair<B, CH, R>(ping, smem, lane_off, code2_lds, offset, acc);
+            if (++it >= steps) break;
+            if (it + 1 < steps) load_step<B, CH, R, FULL>(ping, rb, x, log2_bs, K, rows, (it + 1) * kSlice, lane);
+            compute_step_pair<B, CH, R>(pong, smem, lane_off, code2_lds, offset, acc);
+            if (++it >= steps) break;
+        }
     }
 
 #pragma unroll
@@ -353,6 +448,15 @@ static void launch_gemv(const uint8_t* packed, const uint8_t* q8, const float* s
                         hipStream_t s) {
     if (K >= kPairMinK) {
         const unsigned pair_groups = (unsigned)((N + R * kPairWaves - 1) / (R * kPairWaves));
+        if constexpr (CH == 4 && R == 4) {
+            // whole steps, block size 64, 16-bit loads of the scale codes possible: the two-load scale fetch
+            if (K % (8 * CH * kWave) == 0 && N % R == 0 && log2_bs == 6 && aligned(q8, 2) && K < (int64_t(1) << 31)) {
+                hipLaunchKernelGGL((gemv_pair_kernel<B, CH, R, true, true>), dim3(pair_groups),
+                                   dim3(kPairWaves * kWave), 0, s, packed, q8, scale2, offset, code2, log2_bs, N, K,
+                                   (const _Float16*)x, (_Float16*)y);
+                return;
+            }
+        }
         if (K % (8 * CH * kWave) == 0 && N % R == 0)
             hipLaunchKernelGGL((gemv_pair_kernel<B, CH, R, true>), dim3(pair_groups), dim3(kPairWaves * kWave), 0, s,
                                packed, q8, scale2, offset, code2, log2_bs, N, K, (const _Float16*)x, (_Float16*)y);

@@ -82,6 +82,42 @@ def test_unit_vectors_on_long_rows():
         assert np.array_equal(y.view(np.uint16), want.view(np.uint16))
 
 
+@pytest.mark.parametrize("B", [1, 2])
+@pytest.mark.parametrize("N,K", [(8, 16384), (12, 18432), (44, 20480)])
+def test_long_rows_in_whole_steps(N, K, B):
+    """Rows of whole 2048-element steps with a multiple of four rows: the long-row kernel then fetches the scale
+    codes of four rows as one 16-bit load per lane and passes the decoded scales round through LDS.  K / 64 = 256,
+    288 and 320 blocks per row put the boundaries of the 256-block second-level groups at the start of a row, inside
+    a step and between two steps.  Checked against the oracle, element by element against the form that fetches
+    every scale where it is used (taken when the scale codes start at an odd address: bit-identical results), and
+    with unit vectors that pick single weights (exact)."""
+    case = make_case(N, K, seed=3 * N + K)
+    p, q8, s2, off, c2 = case
+    x = synth.activations_fp16(B, K, seed=B + 11)
+    _, ref = oracle.dequant_gemv(*case, N, K, x.view(np.uint16))
+    y = gemv_gpu(case, N, K, x)
+    assert within_bar(y, ref)
+    assert np.abs(y - ref).max() / np.abs(ref).max() < 2e-3
+    # the same call with the scale codes at an odd address
+    shifted = torch.empty(q8.size + 1, dtype=torch.uint8, device="cuda")
+    shifted[1:] = dev(q8)
+    y2 = torch.full((B, N), float("nan"), dtype=torch.float16, device="cuda")
+    nf4.nf4_dequant_gemv(dev(p), shifted[1:], dev(s2), dev(off), dev(c2), 64, N, K, dev(x), B, y2)
+    torch.cuda.synchronize()
+    assert np.array_equal(y2.cpu().numpy().view(np.uint16), y.view(np.uint16))
+    # single weights: every block of three rows, at both ends of the block
+    w = oracle.dequantize_dq(*case, N * K, out_dtype=oracle.FP32).reshape(N, K)
+    ks = [k for blk in range(0, K // 64, 37) for k in (64 * blk, 64 * blk + 63)] + [K - 64, K - 1]
+    for k0 in range(0, len(ks), B):
+        chunk = ks[k0:k0 + B]
+        xu = np.zeros((B, K), np.float16)
+        for b, k in enumerate(chunk):
+            xu[b, k] = 1.0
+        yu = gemv_gpu(case, N, K, xu)
+        want = w[:, chunk].T.astype(np.float16)
+        assert np.array_equal(yu[:len(chunk)].view(np.uint16), want.view(np.uint16)), chunk
+
+
 def test_zero_activations_and_all_ones_weights():
     N, K = 16, 1024
     case = make_case(N, K, seed=6)
