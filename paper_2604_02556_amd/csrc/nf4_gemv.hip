@@ -174,53 +174,70 @@ __device__ __forceinline__ void compute_step(const StepRegs<B, CH, R>& g, const 
     }
 }
 
-// The block scales of a step through two loads instead of eight (block size 64, whole steps, R = 4 rows of
-// CH = 4 dwords per lane: 32 blocks per row and step).  Lane l fetches the two 8-bit codes of blocks 2 (l % 16)
-// and 2 (l % 16) + 1 of row l / 16 as one 16-bit load -- the wave reads the four rows' 32 bytes each in one request
-// -- and their second-level scale (the two blocks share a group: a group starts at an even block), decodes both
-// and leaves them in this wave's LDS slice, where every lane picks up the scale of its own block of each row.
-// Same arithmetic per scale as the per-lane form (table value times second-level scale, rounded, plus offset).
-template <int B>
-__device__ __forceinline__ void load_step_merged(StepRegs<B, 4, 4>& g, const RowBases<4>& rb, uint32_t blocks_per_row,
+// The block scales of a step through two loads instead of eight (block size 64, whole steps, R = 4 rows of CH
+// dwords per lane: 8 CH blocks per row and step).  Sixteen lanes serve a row: lane l fetches the 8-bit codes of
+// CH / 2 consecutive blocks of row l / 16 -- one 16-bit load for CH = 4, one byte for CH = 2; the wave reads the
+// four rows' 32 or 16 bytes each in one request -- and their second-level scale (two blocks fetched together share
+// a group: a group starts at an even block), decodes them and leaves them in this wave's LDS slice, where every
+// lane picks up the scale of its own block of each row.  Same arithmetic per scale as the per-lane form (table
+// value times second-level scale, rounded, plus offset).
+template <int B, int CH>
+__device__ __forceinline__ void load_step_merged(StepRegs<B, CH, 4>& g, const RowBases<4>& rb, uint32_t blocks_per_row,
                                                  const _Float16* __restrict__ x, int64_t K, int64_t k0, int lane) {
+    static_assert(CH == 2 || CH == 4, "one or two blocks per lane");
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    constexpr uint32_t kPer = CH / 2;                              // blocks per fetching lane
     const int64_t kb = k0 >> 6;
-    const uint32_t v = (uint32_t)(lane >> 4) * blocks_per_row + 2u * (uint32_t)(lane & 15);   // blocks past (row 0, kb)
-    g.q8[0] = *(const uint16_t*)(rb.q8[0] + kb + v);
+    const uint32_t v = (uint32_t)(lane >> 4) * blocks_per_row + kPer * (uint32_t)(lane & 15);   // blocks past (row 0, kb)
+    if constexpr (CH == 4) g.q8[0] = *(const uint16_t*)(rb.q8[0] + kb + v);
+    else g.q8[0] = (rb.q8[0] + kb)[v];
     const int64_t gb = (int64_t)rb.blk_lo[0] + kb;
     g.s2[0] = (rb.s2[0] + (gb >> 8))[((uint32_t)(gb & 255) + v) >> 8];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-        const u32x4 c = __builtin_nontemporal_load((const u32x4*)(rb.codes[r] + (k0 >> 1)) + lane);
-        g.q[r][0] = c[0]; g.q[r][1] = c[1]; g.q[r][2] = c[2]; g.q[r][3] = c[3];
+        const uint8_t* codes = rb.codes[r] + (k0 >> 1);
+        if constexpr (CH == 4) {
+            const u32x4 c = __builtin_nontemporal_load((const u32x4*)codes + lane);
+            g.q[r][0] = c[0]; g.q[r][1] = c[1]; g.q[r][2] = c[2]; g.q[r][3] = c[3];
+        } else {
+            const u32x2 c = __builtin_nontemporal_load((const u32x2*)codes + lane);
+            g.q[r][0] = c[0]; g.q[r][1] = c[1];
+        }
     }
 #pragma unroll
     for (int b = 0; b < B; ++b) {
         const half8_t* xb = (const half8_t*)(x + (int64_t)b * K + k0);
 #pragma unroll
-        for (int c = 0; c < 4; ++c) g.xh[b][c] = xb[lane * 4 + c];
+        for (int c = 0; c < CH; ++c) g.xh[b][c] = xb[lane * CH + c];
     }
 }
 
-// Decode the two scales this lane fetched, hand them round through the wave's LDS slice (R x 32 floats) and pick
-// up the scale of this lane's own block of each row.
-__device__ __forceinline__ void merged_scales(uint32_t q8_pair, float s2, const float* code2_lds, float offset,
+// Decode the scales this lane fetched, hand them round through the wave's LDS slice (4 rows x 8 CH floats) and
+// pick up the scale of this lane's own block of each row.
+template <int CH>
+__device__ __forceinline__ void merged_scales(uint32_t q8_codes, float s2, const float* code2_lds, float offset,
                                               float* wave_scales, int lane, float (&sc)[4]) {
-    const float pa = code2_lds[q8_pair & 255u] * s2;               // rounded product, then rounded sum
-    const float pb = code2_lds[q8_pair >> 8] * s2;
-    *(float2_t*)&wave_scales[2 * lane] = (float2_t){pa + offset, pb + offset};   // [row l / 16][block 2 (l % 16)]
+    const float pa = code2_lds[q8_codes & 255u] * s2;              // rounded product, then rounded sum
+    if constexpr (CH == 4) {
+        const float pb = code2_lds[q8_codes >> 8] * s2;
+        *(float2_t*)&wave_scales[2 * lane] = (float2_t){pa + offset, pb + offset};   // [row l / 16][block 2 (l % 16)]
+    } else {
+        wave_scales[lane] = pa + offset;                           // [row l / 16][block l % 16]
+    }
     wave_lds_fence();
+    // the lane's 8 CH elements lie in block 8 CH lane / 64 of the step
 #pragma unroll
-    for (int r = 0; r < 4; ++r) sc[r] = wave_scales[32 * r + (lane >> 1)];       // lane's 32 elements: block lane / 2
+    for (int r = 0; r < 4; ++r) sc[r] = wave_scales[8 * CH * r + (lane >> (CH == 4 ? 1 : 2))];
 }
 
 // One step of the long-row kernel with the scales fetched that way.
-template <int B>
-__device__ __forceinline__ void compute_step_merged(const StepRegs<B, 4, 4>& g, const uint8_t* table, uint32_t lane_off,
+template <int B, int CH>
+__device__ __forceinline__ void compute_step_merged(const StepRegs<B, CH, 4>& g, const uint8_t* table, uint32_t lane_off,
                                                     const float* code2_lds, float offset, float* wave_scales,
                                                     int lane, float (&acc)[4][B]) {
-    constexpr int R = 4, CH = 4, U = R * CH;
+    constexpr int R = 4, U = R * CH;
     float sc[R];
-    merged_scales(g.q8[0], g.s2[0], code2_lds, offset, wave_scales, lane, sc);
+    merged_scales<CH>(g.q8[0], g.s2[0], code2_lds, offset, wave_scales, lane, sc);
     float lv[2][8];
     issue_pair_lookups(g.q[0][0], table, lane_off, lv[0]);
     float part[B];
@@ -370,8 +387,8 @@ __global__ __launch_bounds__(kPairWaves * kWave) void gemv_pair_kernel(const uin
     constexpr int kSlice = E * kWave;
     constexpr int kThreads = kPairWaves * kWave;
     // one LDS object, so that the pair table sits at address 0: table | 16 levels | code2
-    static_assert(!MERGED || (FULL && CH == 4 && R == 4), "the two-load scale fetch is for whole steps of 4 x 4 dwords");
-    constexpr int kScaleBytes = MERGED ? kPairWaves * R * 32 * 4 : 0;   // per wave: R rows x 32 block scales
+    static_assert(!MERGED || (FULL && (CH == 4 || CH == 2) && R == 4), "the two-load scale fetch is for whole steps of four rows");
+    constexpr int kScaleBytes = MERGED ? kPairWaves * R * 8 * CH * 4 : 0;   // per wave: R rows x 8 CH block scales
     __shared__ __attribute__((aligned(16))) uint8_t smem[kPairTableBytes + 64 + 1024 + kScaleBytes];
     float* lut = (float*)(smem + kPairTableBytes);
     float* code2_lds = (float*)(smem + kPairTableBytes + 64);
@@ -410,15 +427,15 @@ __global__ __launch_bounds__(kPairWaves * kWave) void gemv_pair_kernel(const uin
     }
     StepRegs<B, CH, R> ping, pong;
     if constexpr (MERGED) {
-        float* wave_scales = (float*)(smem + kPairTableBytes + 64 + 1024) + wave * (R * 32);
+        float* wave_scales = (float*)(smem + kPairTableBytes + 64 + 1024) + wave * (R * 8 * CH);
         const uint32_t blocks_per_row = (uint32_t)(K >> 6);
-        load_step_merged<B>(ping, rb, blocks_per_row, x, K, 0, lane);
+        load_step_merged<B, CH>(ping, rb, blocks_per_row, x, K, 0, lane);
         for (int64_t it = 0;;) {
-            if (it + 1 < steps) load_step_merged<B>(pong, rb, blocks_per_row, x, K, (it + 1) * kSlice, lane);
-            compute_step_merged<B>(ping, smem, lane_off, code2_lds, offset, wave_scales, lane, acc);
+            if (it + 1 < steps) load_step_merged<B, CH>(pong, rb, blocks_per_row, x, K, (it + 1) * kSlice, lane);
+            compute_step_merged<B, CH>(ping, smem, lane_off, code2_lds, offset, wave_scales, lane, acc);
             if (++it >= steps) break;
-            if (it + 1 < steps) load_step_merged<B>(ping, rb, blocks_per_row, x, K, (it + 1) * kSlice, lane);
-            compute_step_merged<B>(pong, smem, lane_off, code2_lds, offset, wave_scales, lane, acc);
+            if (it + 1 < steps) load_step_merged<B, CH>(ping, rb, blocks_per_row, x, K, (it + 1) * kSlice, lane);
+            compute_step_merged<B, CH>(pong, smem, lane_off, code2_lds, offset, wave_scales, lane, acc);
             if (++it >= steps) break;
         }
     } else {
@@ -448,9 +465,10 @@ static void launch_gemv(const uint8_t* packed, const uint8_t* q8, const float* s
                         hipStream_t s) {
     if (K >= kPairMinK) {
         const unsigned pair_groups = (unsigned)((N + R * kPairWaves - 1) / (R * kPairWaves));
-        if constexpr (CH == 4 && R == 4) {
-            // whole steps, block size 64, 16-bit loads of the scale codes possible: the two-load scale fetch
-            if (K % (8 * CH * kWave) == 0 && N % R == 0 && log2_bs == 6 && aligned(q8, 2) && K < (int64_t(1) << 31)) {
+        if constexpr ((CH == 4 || CH == 2) && R == 4) {
+            // whole steps, block size 64, the scale codes loadable in pairs: the two-load scale fetch
+            if (K % (8 * CH * kWave) == 0 && N % R == 0 && log2_bs == 6 && aligned(q8, 2) && K % 128 == 0 &&
+                K < (int64_t(1) << 31)) {
                 hipLaunchKernelGGL((gemv_pair_kernel<B, CH, R, true, true>), dim3(pair_groups),
                                    dim3(kPairWaves * kWave), 0, s, packed, q8, scale2, offset, code2, log2_bs, N, K,
                                    (const _Float16*)x, (_Float16*)y);

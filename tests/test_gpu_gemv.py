@@ -82,13 +82,13 @@ def test_unit_vectors_on_long_rows():
         assert np.array_equal(y.view(np.uint16), want.view(np.uint16))
 
 
-@pytest.mark.parametrize("B", [1, 2])
-@pytest.mark.parametrize("N,K", [(8, 16384), (12, 18432), (44, 20480)])
+@pytest.mark.parametrize("B", [1, 2, 3, 4, 5, 6])
+@pytest.mark.parametrize("N,K", [(8, 16384), (12, 18432), (44, 20480), (8, 17408)])
 def test_long_rows_in_whole_steps(N, K, B):
-    """Rows of whole 2048-element steps with a multiple of four rows: the long-row kernel then fetches the scale
-    codes of four rows as one 16-bit load per lane and passes the decoded scales round through LDS.  K / 64 = 256,
-    288 and 320 blocks per row put the boundaries of the 256-block second-level groups at the start of a row, inside
-    a step and between two steps.  Checked against the oracle, element by element against the form that fetches
+    """Rows of whole steps (2048 elements for one or two tokens, 1024 for three to six) with a multiple of four
+    rows: the long-row kernel then fetches the scale codes of four rows in one load per lane and passes the decoded
+    scales round through LDS.  K / 64 = 256, 288, 320 and 272 blocks per row put the boundaries of the 256-block
+    second-level groups at the start of a row, inside a step and between two steps.  Checked against the oracle, element by element against the form that fetches
     every scale where it is used (taken when the scale codes start at an odd address: bit-identical results), and
     with unit vectors that pick single weights (exact)."""
     case = make_case(N, K, seed=3 * N + K)
