@@ -353,10 +353,12 @@ def leg_gemv(torch, nf4, synth, stream, gen, src):
             tflops = 2.0 * B * n / (us * 1e-6) / 1e12
             entry = {"us": round(us, 2), "GB/s": round(gbps, 1), "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
                      "TFLOP/s": round(tflops, 2), "bound": "alu"}
-            if B < 7:       # vector-ALU FMAs; from 7 tokens on the entry point uses the matrix cores and the
-                entry["frac_of_fp32_fma_peak"] = round(tflops / FP32_FMA_PEAK_TFLOPS, 4)   # ALU work is the expansion
+            if B < (3 if N < 16384 else 5):     # vector-ALU FMAs; for more tokens the entry point uses the matrix cores
+                entry["frac_of_fp32_fma_peak"] = round(tflops / FP32_FMA_PEAK_TFLOPS, 4)
             else:
-                entry["kernel"] = "matrix cores, weight as two FP16 terms; bound by the expansion of the codes"
+                entry["kernel"] = ("matrix cores, levels as two FP16 terms, FP32 block scales; bound by LDS lookups "
+                                   "and, at 16 tokens, by every workgroup re-reading the activations from L2")
+                entry["bound"] = "lds/l2"
             res[f"N{N}_K{K}_B{B}"] = entry
         # the matrix-core variant (weights rounded to FP16 in registers), the paper's batch range
         for B in GEMM_BATCHES:

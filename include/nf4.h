@@ -116,9 +116,12 @@ int nf4_dequantize_batch(const nf4_tensor* tensors, int count, int blocksize, in
  * FP32 accumulation, W is [N][K] row-major with double-quantised scales as in
  * nf4_dequantize_dq.  x : FP16 [B][K], y : FP16 [B][N], 1 <= B <= 16, K > 0
  * and K % blocksize == 0 (else NF4_ERR_SHAPE).  packed and x must be 16-byte
- * aligned.  Up to 6 tokens W stays the FP32 product (vector-ALU FMAs); from 7
- * tokens on the sum runs on the matrix cores with W as two FP16 terms, i.e. to
- * 22 significant bits, which needs |W| < 65504.
+ * aligned.  For one or two tokens (up to four when N >= 16384) W stays the FP32
+ * product (vector-ALU FMAs).  For more tokens the sum runs on the matrix cores:
+ * every level enters them as two FP16 terms (the level to about 2^-22
+ * relative), the products of a quantisation block are summed unscaled in FP32
+ * and the block's FP32 scale multiplies that sum, so W is carried to about 22
+ * significant bits whatever its magnitude.
  */
 int nf4_dequant_gemv(const uint8_t* packed, const uint8_t* absmax_q8, const float* scale2,
                      const float* offset, const float* code2, int blocksize, int64_t N,

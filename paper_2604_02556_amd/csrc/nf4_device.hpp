@@ -85,20 +85,6 @@ __device__ __forceinline__ uint32_t scaled_pack2_f16(float lo, float hi, float s
     return __builtin_bit_cast(uint32_t, h);
 }
 
-// The product a * s carried as two FP16 terms for the matrix cores:
-// hi = rne_fp16(a * s) (the exact product, one rounding), lo = rne_fp16(a * s - hi)
-// (one fused operation, so the residual is formed from the exact product).  hi + lo reproduces the product to
-// about 2^-22 relative (2^-25 absolute where lo is an FP16 subnormal); it needs
-// |a * s| < 65504.  Two mixed-precision instructions per value.
-__device__ __forceinline__ void two_term_pack2_f16(float a0, float a1, float s, float neg_zero, uint32_t& hi,
-                                                   uint32_t& lo) {
-    const _Float16 h0 = (_Float16)__builtin_fmaf(a0, s, neg_zero), h1 = (_Float16)__builtin_fmaf(a1, s, neg_zero);
-    const _Float16 l0 = (_Float16)__builtin_fmaf(a0, s, -(float)h0), l1 = (_Float16)__builtin_fmaf(a1, s, -(float)h1);
-    const half2_t h = {h0, h1}, l = {l0, l1};
-    hi = __builtin_bit_cast(uint32_t, h);
-    lo = __builtin_bit_cast(uint32_t, l);
-}
-
 // One value.  The empty asm pins `v` as a finished FP32 result: without it the
 // compiler folds a preceding multiply into a mixed-precision multiply-add with
 // a +0 addend, which turns a product of -0 into +0.

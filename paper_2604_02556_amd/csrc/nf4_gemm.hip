@@ -44,12 +44,31 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kRowStride = 36;               // dwords per row in the exchange buffer (32 + padding)
 
-// TWO_TERM: the weight enters the matrix cores as two FP16 terms (hi + lo, see two_term_pack2_f16), i.e. as the
-// FP32 product level * scale to 22 bits instead of rounded to FP16 -- the GEMV's definition of W, used by
-// nf4_dequant_gemv for more than 8 tokens.
+// SPLIT = false: the weight enters the matrix cores as rne_fp16(level * scale), the GEMM's definition of W.
+// SPLIT = true: the FP32 product level * scale, the GEMV's definition of W, without any arithmetic per weight: the
+//   table holds every LEVEL as two FP16 terms (hi + lo = the level to about 2^-22), the lookups deliver the MFMA
+//   operands as they are, an MFMA step's 32 k lie in one quantisation block, so the products of a block are summed
+//   unscaled (hi and lo into the same tile) and the block's FP32 scale multiplies the tile afterwards: four FMAs
+//   per lane and block instead of mixed-precision instructions per weight, and the scale is never narrowed (no
+//   bound on |W|, no underflow of small scales).  Needs the pair table's space (PAIR).  nf4_dequant_gemv uses it.
 // PAIR: levels come from the byte-indexed pair table (issue_pair_lookups) instead of the 16-entry table: fewer
 // instructions, 64 KiB more LDS (the final reduction buffer shares that space).
-template <int TG, int RG, int kMWaves, bool TWO_TERM, bool PAIR>
+
+// The split table: entry [byte][replica] = (half2(hi(level[byte >> 4]), hi(level[byte & 15])),
+// half2(lo(..), lo(..))) with hi = rne_fp16(level), lo = rne_fp16(level - hi) (the difference is exact in FP32):
+// hi + lo is the level to about 2^-22 relative.  Same shape and addressing as the pair table.
+__device__ __forceinline__ void fill_split_table(float2_t* table, const float* lut, int tid, int threads) {
+    for (int i = tid; i < 256 * kPairReplicas; i += threads) {
+        const int byte = i / kPairReplicas;
+        const float e = lut[byte >> 4], o = lut[byte & 15];
+        const _Float16 eh = (_Float16)e, oh = (_Float16)o;
+        const half2_t hi = {eh, oh};
+        const half2_t lo = {(_Float16)(e - (float)eh), (_Float16)(o - (float)oh)};
+        table[i] = (float2_t){__builtin_bit_cast(float, hi), __builtin_bit_cast(float, lo)};
+    }
+}
+
+template <int TG, int RG, int kMWaves, bool SPLIT, bool PAIR>
 __global__ __launch_bounds__(kMWaves * kWave) void gemm_kernel(const uint8_t* __restrict__ packed,
                                                                const uint8_t* __restrict__ q8,
                                                                const float* __restrict__ scale2,
@@ -75,8 +94,10 @@ __global__ __launch_bounds__(kMWaves * kWave) void gemm_kernel(const uint8_t* __
     if (tid < 16) lut[tid] = __uint_as_float(level_literal(tid));
     for (int i = tid; i < 256; i += kMThreads) code2_lds[i] = code2[i];
     __syncthreads();
+    static_assert(!SPLIT || PAIR, "the split levels live in the pair table's space");
     if constexpr (PAIR) {
-        fill_pair_table((float2_t*)smem, lut, tid, kMThreads);
+        if constexpr (SPLIT) fill_split_table((float2_t*)smem, lut, tid, kMThreads);
+        else fill_pair_table((float2_t*)smem, lut, tid, kMThreads);
         __syncthreads();
     }
     const float offset = offset_p[0];
@@ -140,16 +161,63 @@ __global__ __launch_bounds__(kMWaves * kWave) void gemm_kernel(const uint8_t* __
             // ---- codes cross lanes: group j of the row goes to dwords 4 j .. 4 j + 3; lane group g reads dword g
             *(u32x4*)(my_row + 4 * g) = c[r][0];
             *(u32x4*)(my_row + 4 * (g + 4)) = c[r][1];
+            if constexpr (SPLIT)                 // scale of (row sub, quarter g) -> row 4 g + sub / 4, element sub % 4
+                *(float*)(my_row - sub * kRowStride + (4 * g + (sub >> 2)) * kRowStride + 32 + (sub & 3)) = mine[r];
             wave_lds_fence();
             uint32_t q[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) q[j] = my_row[4 * j + g];
             float s[4];                          // quarter jj of the window: k = 64 jj .. -> MFMA steps 2 jj, 2 jj + 1
+            if constexpr (!SPLIT) {
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj)
-                s[jj] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((sub + 16 * jj) << 2,
-                                                                               __builtin_bit_cast(int, mine[r])));
+                for (int jj = 0; jj < 4; ++jj)
+                    s[jj] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((sub + 16 * jj) << 2,
+                                                                                   __builtin_bit_cast(int, mine[r])));
+            }
 
+            if constexpr (SPLIT) {
+                // The block scales in the layout of the C tile: lane (token, g) needs those of rows 4 g .. 4 g + 3.
+                // They travel in the padding of the exchange rows: row 4 q + g' holds, for quarter q, the scales of
+                // rows 4 g' .. 4 g' + 3 (written above, with the codes).
+                f32x4 sc[4];
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj)
+                    sc[jj] = *(const f32x4*)(my_row - sub * kRowStride + (4 * jj + g) * kRowStride + 32);
+                const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
+                f32x4 blk[TG];
+                float lv[2][8];
+                lookups(q[0], lv[0]);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    if (j + 1 < 8) {
+                        lookups(q[j + 1], lv[(j + 1) & 1]);
+                        lds_wait<kPerDword>();
+                    } else {
+                        lds_wait<0>();
+                    }
+                    u32x4 a, a_lo;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        a[i] = __builtin_bit_cast(uint32_t, lv[j & 1][2 * i]);
+                        a_lo[i] = __builtin_bit_cast(uint32_t, lv[j & 1][2 * i + 1]);
+                    }
+                    const half8_t ah = __builtin_bit_cast(half8_t, a), al = __builtin_bit_cast(half8_t, a_lo);
+#pragma unroll
+                    for (int t = 0; t < TG; ++t) {
+                        blk[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah, xb[t][j], (j & 1) ? blk[t] : zero, 0, 0, 0);
+                        blk[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(al, xb[t][j], blk[t], 0, 0, 0);
+                    }
+                    if (j & 1) {                 // both halves of quarter j / 2 are in: scale the tile
+#pragma unroll
+                        for (int t = 0; t < TG; ++t)
+#pragma unroll
+                            for (int i = 0; i < 4; ++i)
+                                acc[r][t][i] = __builtin_fmaf(sc[j >> 1][i], blk[t][i], acc[r][t][i]);
+                    }
+                }
+                wave_lds_fence();                // the exchange buffer is overwritten next
+                continue;
+            }
             // ---- dequantise to FP16 in registers and multiply: lookups pipelined two dwords deep
             float lv[2][8];
             lookups(q[0], lv[0]);
@@ -162,28 +230,13 @@ __global__ __launch_bounds__(kMWaves * kWave) void gemm_kernel(const uint8_t* __
                     lds_wait<0>();
                 }
                 const float sj = s[j >> 1];
-                u32x4 a, a_lo;
+                u32x4 a;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    if constexpr (TWO_TERM) {
-                        uint32_t hi, lo;
-                        two_term_pack2_f16(lv[j & 1][2 * i], lv[j & 1][2 * i + 1], sj, nz, hi, lo);
-                        a[i] = hi;
-                        a_lo[i] = lo;
-                    } else {
-                        a[i] = scaled_pack2_f16(lv[j & 1][2 * i], lv[j & 1][2 * i + 1], sj, nz);
-                    }
-                }
+                for (int i = 0; i < 4; ++i) a[i] = scaled_pack2_f16(lv[j & 1][2 * i], lv[j & 1][2 * i + 1], sj, nz);
                 const half8_t ah = __builtin_bit_cast(half8_t, a);
 #pragma unroll
                 for (int t = 0; t < TG; ++t)
                     acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah, xb[t][j], acc[r][t], 0, 0, 0);
-                if constexpr (TWO_TERM) {
-                    const half8_t al = __builtin_bit_cast(half8_t, a_lo);
-#pragma unroll
-                    for (int t = 0; t < TG; ++t)
-                        acc[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(al, xb[t][j], acc[r][t], 0, 0, 0);
-                }
             }
             wave_lds_fence();                    // the exchange buffer is overwritten next
         }
@@ -210,23 +263,22 @@ __global__ __launch_bounds__(kMWaves * kWave) void gemm_kernel(const uint8_t* __
     }
 }
 
-template <int TG, int RG, int W, bool TWO_TERM = false, bool PAIR = false>
+template <int TG, int RG, int W, bool SPLIT = false, bool PAIR = false>
 static void launch_gemm(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
                         const float* code2, int log2_bs, int64_t N, int64_t K, const _Float16* x, int B,
                         _Float16* y, hipStream_t s) {
     const unsigned groups = (unsigned)((N + 16 * RG - 1) / (16 * RG));
-    hipLaunchKernelGGL((gemm_kernel<TG, RG, W, TWO_TERM, PAIR>), dim3(groups), dim3(W * kWave), 0, s, packed, q8, scale2, offset, code2,
+    hipLaunchKernelGGL((gemm_kernel<TG, RG, W, SPLIT, PAIR>), dim3(groups), dim3(W * kWave), 0, s, packed, q8, scale2, offset, code2,
                        log2_bs, N, K, x, B, y);
 }
 
-// y = x W^T with W = level * scale carried to 22 bits (two FP16 terms) on the matrix cores, at most 16 tokens.
+// y = x W^T with W = level * scale on the matrix cores (levels as two FP16 terms, FP32 block scales), at most 16
+// tokens.  One shape for all matrices: two row groups per workgroup of 16 waves (four and one row groups, and 8
+// waves, all measured slower on 28672 x 8192: 77, 62-92 and more us against 54-56).
 int launch_gemv_mfma(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
                      const float* code2, int log2_bs, int64_t N, int64_t K, const _Float16* x, int B, _Float16* y,
                      hipStream_t s) {
-    // the pair table pays where its 64 KiB of LDS do not cost a resident workgroup (measured: 72 -> 66 us on
-    // 8192 x 28672; the 8-wave form for tall matrices goes from 79 to 98 us with it)
-    if (N >= 16384) launch_gemm<1, 2, 8, true>(packed, q8, scale2, offset, code2, log2_bs, N, K, x, B, y, s);
-    else launch_gemm<1, 2, 16, true, true>(packed, q8, scale2, offset, code2, log2_bs, N, K, x, B, y, s);
+    launch_gemm<1, 2, 16, true, true>(packed, q8, scale2, offset, code2, log2_bs, N, K, x, B, y, s);
     return record_hip(hipGetLastError());
 }
 

@@ -4,10 +4,11 @@
 // handful of tokens that temporary is the dominant traffic, so it is never
 // written here).
 //
-// Up to 6 tokens this is not a dense contraction, so no MFMA: FP32 FMAs and
-// wave64 DPP reductions, the kernel of this file.  From 7 tokens on the entry
-// point hands the same sum to the matrix-core kernel of nf4_gemm.hip with the
-// FP32 weight carried as two FP16 terms.  Layout of the work here:
+// For one or two tokens (up to four on matrices of 16384 rows and more) this is
+// not a dense contraction, so no MFMA: FP32 FMAs and wave64 DPP reductions, the
+// kernels of this file.  For more tokens the entry point hands the same sum to
+// the matrix-core kernel of nf4_gemm.hip with every level carried as two FP16
+// terms and the block scale applied in FP32.  Layout of the work here:
 //   * one wave owns R consecutive rows of W over the whole of K, so no partial
 //     sums ever leave the wave and the summation order is fixed (deterministic
 //     results); the grid is one-shot.  Short rows: single-wave workgroups
@@ -501,8 +502,7 @@ static int gemv_tokens(const uint8_t* packed, const uint8_t* q8, const float* sc
     switch (B) {
         // (tokens, code dwords per lane per row, rows per wave): picked by sweeping on MI355X
         NF4_GEMV_CASE(1, 4, 4) NF4_GEMV_CASE(2, 4, 4) NF4_GEMV_CASE(3, 2, 4) NF4_GEMV_CASE(4, 2, 4)
-        NF4_GEMV_CASE(5, 2, 4) NF4_GEMV_CASE(6, 2, 4)
-        default: return NF4_ERR_SHAPE;
+        default: return NF4_ERR_SHAPE;           // more tokens go to the matrix cores (mfma_min_tokens)
     }
 #undef NF4_GEMV_CASE
     return record_hip(hipGetLastError());
@@ -511,9 +511,11 @@ static int gemv_tokens(const uint8_t* packed, const uint8_t* q8, const float* sc
 }  // namespace nf4
 
 namespace nf4 {
-// Measured on MI355X (8192 x 28672): the FMA kernel takes 30 / 65 / ~80 / ~100 us at 1 / 4 / 6 / 8 tokens, the
-// matrix-core kernel 78-88 us whatever the count.
-constexpr int kMfmaMinTokens = 7;
+// Where the matrix-core kernel takes over, measured on MI355X (us per call, FMA kernels / matrix cores):
+//   8192 x 28672:  2 tokens 38.9 / 42.7,  3 tokens 46.1 / 43.2,  4 tokens 54.3 / 43.2,  6 tokens 65.7 / 43.9
+//   28672 x 8192:  3 tokens 44.8 / 54.9,  4 tokens 54.0 / 55.4,  5 tokens 62.3 / 55.4,  6 tokens 76.3 / 56.2
+// (matrices of 16384 rows and more run it with more workgroups than stay resident, which costs it 12 us).
+static int mfma_min_tokens(int64_t N) { return N < 16384 ? 3 : 5; }
 }
 
 extern "C" int nf4_dequant_gemv(const uint8_t* packed, const uint8_t* absmax_q8, const float* scale2,
@@ -535,10 +537,10 @@ extern "C" int nf4_dequant_gemv(const uint8_t* packed, const uint8_t* absmax_q8,
         !aligned(code2, 4))
         return NF4_ERR_ALIGN;
 
-    // From kMfmaMinTokens tokens on the sum is a dense enough contraction for the matrix cores: the FP32 weight
-    // level * scale enters them as two FP16 terms (22 significant bits, see two_term_pack2_f16), the activations
-    // as they are, accumulation in FP32.  Below that, FMAs on the vector ALU with the weight never narrowed.
-    if (B >= kMfmaMinTokens)
+    // From mfma_min_tokens tokens on the sum goes to the matrix cores: the levels enter them as two FP16 terms
+    // (22 significant bits), the activations as they are, the block scale multiplies each block's partial sums in
+    // FP32, accumulation in FP32.  Below that, FMAs on the vector ALU with the FP32 weight never narrowed.
+    if (B >= mfma_min_tokens(N))
         return launch_gemv_mfma(packed, absmax_q8, scale2, offset, code2, log2_bs, N, K, (const _Float16*)x, B,
                                 (_Float16*)y, s);
     return gemv_tokens(packed, absmax_q8, scale2, offset, code2, log2_bs, N, K, (const _Float16*)x, B,
