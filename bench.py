@@ -360,6 +360,19 @@ def leg_gemv(torch, nf4, synth, stream, gen, src):
                                    "and, at 16 tokens, by every workgroup re-reading the activations from L2")
                 entry["bound"] = "lds/l2"
             res[f"N{N}_K{K}_B{B}"] = entry
+            if B >= 3:      # with a caller workspace K is split across workgroups (nf4_dequant_gemv_ws)
+                ws = torch.empty(nf4.nf4_dequant_gemv_workspace_bytes(N, K, B), dtype=torch.uint8, device=dev)
+
+                def run_ws():
+                    for b in copies:
+                        nf4.nf4_dequant_gemv_ws(b["packed"], b["absmax_q8"], b["scale2"], b["offset"], b["code2"], 64,
+                                                N, K, x, B, y, ws, stream=stream)
+                us = time_on_stream(torch, stream, run_ws, 5) / len(copies)
+                gbps = n * GEMV_BYTES_PER_ELEM / (us * 1e-6) / 1e9
+                res[f"ws_N{N}_K{K}_B{B}"] = {"us": round(us, 2), "GB/s": round(gbps, 1),
+                                             "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
+                                             "TFLOP/s": round(2.0 * B * n / (us * 1e-6) / 1e12, 2),
+                                             "workspace_bytes": int(ws.numel())}
         # the matrix-core variant (weights rounded to FP16 in registers), the paper's batch range
         for B in GEMM_BATCHES:
             gen.manual_seed(6100 + B)

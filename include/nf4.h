@@ -128,6 +128,27 @@ int nf4_dequant_gemv(const uint8_t* packed, const uint8_t* absmax_q8, const floa
                      int64_t K, const void* x, int B, void* y, void* stream);
 
 /*
+ * nf4_dequant_gemv with a workspace (device, 16-byte aligned, owned by the
+ * caller, contents undefined before and after; at least
+ * nf4_dequant_gemv_workspace_bytes(N, K, B) bytes, else NF4_ERR_SIZE; NULL is
+ * NF4_ERR_NULL).  Same definition of y, same arguments, layouts and limits.
+ * From 3 tokens on, K is split across workgroups that share the activations
+ * through LDS; FP32 partial sums go to the workspace and a second kernel adds
+ * them in a fixed order (deterministic).  W is carried as on the matrix-core
+ * path above (levels as two FP16 terms, FP32 block scales).  About 40 us for 3
+ * to 16 tokens on the 70B MLP shapes, where nf4_dequant_gemv takes 41 to 70.
+ * Calls that share a workspace must not overlap.
+ */
+int nf4_dequant_gemv_ws(const uint8_t* packed, const uint8_t* absmax_q8, const float* scale2,
+                        const float* offset, const float* code2, int blocksize, int64_t N,
+                        int64_t K, const void* x, int B, void* y, void* workspace,
+                        size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace nf4_dequant_gemv_ws needs for this shape on the current
+ * device (0 for shapes it rejects). */
+size_t nf4_dequant_gemv_workspace_bytes(int64_t N, int64_t K, int B);
+
+/*
  * Fused dequantise + small-batch GEMM on the matrix cores, for the paper's batch
  * range (Sec. VI-A: 2 to 64).  It is the paper's quantised matmul (Sec. III-A,
  * III-C: dequantise W to FP16, then an FP16 matmul with FP32 accumulation)

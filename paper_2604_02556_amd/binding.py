@@ -52,6 +52,10 @@ def lib():
     L.nf4_dequant_gemm.restype = i32
     L.nf4_dequant_gemm_workspace_bytes.argtypes = [i64, i64, i32]
     L.nf4_dequant_gemm_workspace_bytes.restype = c.c_size_t
+    L.nf4_dequant_gemv_ws.argtypes = [vp, vp, vp, vp, vp, i32, i64, i64, vp, i32, vp, vp, c.c_size_t, vp]
+    L.nf4_dequant_gemv_ws.restype = i32
+    L.nf4_dequant_gemv_workspace_bytes.argtypes = [i64, i64, i32]
+    L.nf4_dequant_gemv_workspace_bytes.restype = c.c_size_t
     L.nf4_quantize_ref.argtypes = [vp, i64, i32, vp, vp, vp, vp, vp, vp, vp]
     L.nf4_dequantize_codebook.argtypes = [vp, vp, vp, i32, i64, vp, i32, vp]
     L.nf4_dequantize_dq_codebook.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, i64, vp, i32, vp]
@@ -155,6 +159,19 @@ def nf4_dequant_gemv(packed, absmax_q8, scale2, offset, code2, blocksize, N, K, 
     _check(lib().nf4_dequant_gemv(_ptr(packed), _ptr(absmax_q8), _ptr(scale2), _ptr(offset), _ptr(code2),
                                   blocksize, N, K, _ptr(x), B, _ptr(y), _stream(stream)))
     return y
+
+
+def nf4_dequant_gemv_ws(packed, absmax_q8, scale2, offset, code2, blocksize, N, K, x, B, y, workspace, stream=None):
+    """workspace: a device tensor of at least nf4_dequant_gemv_workspace_bytes(N, K, B) bytes."""
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().nf4_dequant_gemv_ws(_ptr(packed), _ptr(absmax_q8), _ptr(scale2), _ptr(offset), _ptr(code2),
+                                     blocksize, N, K, _ptr(x), B, _ptr(y), _ptr(workspace), ws_bytes,
+                                     _stream(stream)))
+    return y
+
+
+def nf4_dequant_gemv_workspace_bytes(N, K, B):
+    return int(lib().nf4_dequant_gemv_workspace_bytes(N, K, B))
 
 
 def nf4_dequant_gemm(packed, absmax_q8, scale2, offset, code2, blocksize, N, K, x, B, y, workspace=None,

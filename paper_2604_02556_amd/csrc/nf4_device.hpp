@@ -126,6 +126,20 @@ __device__ __forceinline__ void fill_pair_table(float2_t* table, const float* lu
     }
 }
 
+// The split table: entry [byte][replica] = (half2(hi(level[byte >> 4]), hi(level[byte & 15])),
+// half2(lo(..), lo(..))) with hi = rne_fp16(level), lo = rne_fp16(level - hi) (the difference is exact in FP32):
+// hi + lo is the level to about 2^-22 relative.  Same shape and addressing as the pair table.
+__device__ __forceinline__ void fill_split_table(float2_t* table, const float* lut, int tid, int threads) {
+    for (int i = tid; i < 256 * kPairReplicas; i += threads) {
+        const int byte = i / kPairReplicas;
+        const float e = lut[byte >> 4], o = lut[byte & 15];
+        const _Float16 eh = (_Float16)e, oh = (_Float16)o;
+        const half2_t hi = {eh, oh};
+        const half2_t lo = {(_Float16)(e - (float)eh), (_Float16)(o - (float)oh)};
+        table[i] = (float2_t){__builtin_bit_cast(float, hi), __builtin_bit_cast(float, lo)};
+    }
+}
+
 __device__ __forceinline__ void issue_pair_lookups(uint32_t q, const uint8_t* table, uint32_t lane_off,
                                                    float (&lv)[8]) {
 #pragma unroll

@@ -54,20 +54,6 @@ constexpr int kRowStride = 36;               // dwords per row in the exchange b
 // PAIR: levels come from the byte-indexed pair table (issue_pair_lookups) instead of the 16-entry table: fewer
 // instructions, 64 KiB more LDS (the final reduction buffer shares that space).
 
-// The split table: entry [byte][replica] = (half2(hi(level[byte >> 4]), hi(level[byte & 15])),
-// half2(lo(..), lo(..))) with hi = rne_fp16(level), lo = rne_fp16(level - hi) (the difference is exact in FP32):
-// hi + lo is the level to about 2^-22 relative.  Same shape and addressing as the pair table.
-__device__ __forceinline__ void fill_split_table(float2_t* table, const float* lut, int tid, int threads) {
-    for (int i = tid; i < 256 * kPairReplicas; i += threads) {
-        const int byte = i / kPairReplicas;
-        const float e = lut[byte >> 4], o = lut[byte & 15];
-        const _Float16 eh = (_Float16)e, oh = (_Float16)o;
-        const half2_t hi = {eh, oh};
-        const half2_t lo = {(_Float16)(e - (float)eh), (_Float16)(o - (float)oh)};
-        table[i] = (float2_t){__builtin_bit_cast(float, hi), __builtin_bit_cast(float, lo)};
-    }
-}
-
 template <int TG, int RG, int kMWaves, bool SPLIT, bool PAIR>
 __global__ __launch_bounds__(kMWaves * kWave) void gemm_kernel(const uint8_t* __restrict__ packed,
                                                                const uint8_t* __restrict__ q8,
@@ -314,7 +300,7 @@ extern "C" int nf4_dequant_gemm(const uint8_t* packed, const uint8_t* absmax_q8,
         if (!aligned(workspace, 16)) return NF4_ERR_ALIGN;
         if (workspace_bytes < nf4_dequant_gemm_workspace_bytes(N, K, B)) return NF4_ERR_SIZE;
         return launch_gemm_splitk(packed, absmax_q8, scale2, offset, code2, log2_bs, N, K, xp, B, yp,
-                                  (float*)workspace, s);
+                                  (float*)workspace, false, s);
     }
     // (token groups, row groups per wave, waves per workgroup = split of K), picked by sweeping on MI355X:
     // sharing the activation registers between row groups halves the L2 traffic that bounds this kernel,

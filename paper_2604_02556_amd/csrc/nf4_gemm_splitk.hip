@@ -35,6 +35,13 @@
 // opposite phases and dedicated loader waves that bring the data straight into
 // LDS were each built and measured: no gain.
 //
+// SPLIT = true carries the GEMV's weights through the same kernel (nf4_dequant_gemv_ws): the table holds every
+// level as two FP16 terms, lane group g takes dword g of each 16-byte piece instead of whole pieces -- so that the
+// 32 k of an MFMA step, 128 h + 32 p + 8 g .., lie in one quantisation block --, the products of a block go
+// unscaled into one tile (hi and lo terms, two steps) and the block's FP32 scales, handed from the loading lanes
+// to the layout of the C tile through a small per-wave LDS buffer, multiply the tile into the accumulator.  No
+// arithmetic per weight, the scale never narrowed.  38-41 us for 3 to 16 tokens on the 70B MLP shapes.
+//
 // Since all waves of a workgroup share k, K is split across workgroups instead:
 // blockIdx.y = split s takes `wps` consecutive windows and writes its partial
 // 16 x 16 tiles to partial[s][token][row] (FP32) in the caller's workspace; a
@@ -52,7 +59,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 // and half as many barriers), 256 above that (the activation tiles of 64 tokens would not fit twice in LDS).
 constexpr int window_of(int token_groups) { return token_groups <= 2 ? 512 : 256; }
 
-template <int TG, int RG, int W, int WIN>
+template <int TG, int RG, int W, int WIN, bool SPLIT>
 __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* __restrict__ packed,
                                                                 const uint8_t* __restrict__ q8,
                                                                 const float* __restrict__ scale2,
@@ -75,7 +82,11 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
     // One LDS object, so that the level-pair table sits at address 0 (see issue_pair_lookups):
     // table | two activation tiles | per wave and row group one lane-transpose buffer | code2 | levels
     constexpr int kOffX = kPairTableBytes, kOffTurn = kOffX + 2 * kXTileBytes;
-    constexpr int kOffCode2 = kOffTurn + W * RG * kTurnBytes, kOffLut = kOffCode2 + 1024;
+    // SPLIT (the GEMV's weights, see gemm_kernel in nf4_gemm.hip): per wave and row group the window's block scales
+    // as [quarter][row] floats, read back in the layout of the C tile
+    constexpr int kScaleBytes = SPLIT ? 2 * kH * 16 * 4 : 0;
+    constexpr int kOffScale = kOffTurn + W * RG * kTurnBytes;
+    constexpr int kOffCode2 = kOffScale + W * RG * kScaleBytes, kOffLut = kOffCode2 + 1024;
     __shared__ __attribute__((aligned(16))) uint8_t smem[kOffLut + 64];
     static_assert(sizeof(smem) <= 160 * 1024, "LDS of one compute unit");
     const uint8_t* table = smem;
@@ -87,7 +98,9 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
     if (tid < 16) lut[tid] = __uint_as_float(level_literal(tid));
     for (int i = tid; i < 256; i += kThreads) code2_lds[i] = code2[i];
     __syncthreads();
-    fill_pair_table((float2_t*)smem, lut, tid, kThreads);    // visible after the barrier that follows the first tile
+    // visible after the barrier that follows the first tile
+    if constexpr (SPLIT) fill_split_table((float2_t*)smem, lut, tid, kThreads);
+    else fill_pair_table((float2_t*)smem, lut, tid, kThreads);
     const float offset = offset_p[0];
     const float nz = opaque_neg_zero();
 
@@ -103,6 +116,7 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
     const int lpc = lane & 3;                    //   and 16-byte piece (codes) / 64-element quarter (scales)
     const uint32_t lane_off = pair_lane_offset(lane);
     uint8_t* turn = smem + kOffTurn + wave * (RG * kTurnBytes);   // this wave's transpose buffers
+    float* wave_scales = (float*)(smem + kOffScale + wave * (RG * kScaleBytes));
     const int64_t row0 = ((int64_t)blockIdx.x * W + wave) * (16 * RG);
     const int64_t k_begin = (int64_t)blockIdx.y * wps * WIN;
     const int64_t k_stop = k_begin + (int64_t)wps * WIN;
@@ -223,12 +237,18 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
                 const float prod = code2_lds[cr.qb[r][m]] * cr.s2[r][m];
                 mine[m] = (row0 + 16 * r + lrow < N && kw + 64 * (lpc + 4 * m) < k_end) ? prod + offset : 0.0f;
             }
-            // piece h of the arithmetic lane lies in quarter 2 h + g / 2 of row sub: lane 4 sub + quarter % 4, entry h / 2
+            if constexpr (SPLIT) {
+                // into the wave's scale buffer, [quarter][row]; read back per block in the main loop
 #pragma unroll
-            for (int h = 0; h < kH; ++h)
-                s[r][h] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(
-                                                        (4 * sub + ((2 * h + (g >> 1)) & 3)) << 2,
-                                                        __builtin_bit_cast(int, mine[h >> 1])));
+                for (int m = 0; m < kH / 2; ++m) wave_scales[r * (kScaleBytes / 4) + (lpc + 4 * m) * 16 + lrow] = mine[m];
+            } else {
+                // piece h of the arithmetic lane lies in quarter 2 h + g / 2 of row sub: lane 4 sub + quarter % 4, entry h / 2
+#pragma unroll
+                for (int h = 0; h < kH; ++h)
+                    s[r][h] = __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(
+                                                            (4 * sub + ((2 * h + (g >> 1)) & 3)) << 2,
+                                                            __builtin_bit_cast(int, mine[h >> 1])));
+            }
         }
         // the pieces change lanes one h at a time through the wave's buffer (one per row group)
 #pragma unroll
@@ -237,7 +257,14 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
             for (int r = 0; r < RG; ++r) *(u32x4*)(turn + r * kTurnBytes + lrow * kTurnRow + 16 * lpc) = cr.c[r][h];
             wave_lds_fence();
 #pragma unroll
-            for (int r = 0; r < RG; ++r) c[r][h] = *(const u32x4*)(turn + r * kTurnBytes + sub * kTurnRow + 16 * g);
+            for (int r = 0; r < RG; ++r) {
+                if constexpr (SPLIT) {           // dword g of each of the four pieces: an MFMA step stays in one block
+                    const uint32_t* tp = (const uint32_t*)(turn + r * kTurnBytes + sub * kTurnRow + 4 * g);
+                    c[r][h] = (u32x4){tp[0], tp[4], tp[8], tp[12]};
+                } else {
+                    c[r][h] = *(const u32x4*)(turn + r * kTurnBytes + sub * kTurnRow + 16 * g);
+                }
+            }
             wave_lds_fence();                    // read before the next h overwrites the buffer
         }
 
@@ -245,9 +272,65 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
         load_codes(kw + WIN, nx);
         load_x(kw + WIN);
 
+        constexpr int kSteps = 4 * kH;
+        if constexpr (SPLIT) {
+            // Lane group g holds dword g of every piece: MFMA step j = (h, p) takes k = 128 h + 32 p + 8 g .. + 7, all
+            // inside quarter 2 h + p / 2.  The two steps x two terms (hi, lo) of a quarter go unscaled into one tile,
+            // which the quarter's FP32 scales (rows 4 g .. 4 g + 3 of the C layout) multiply into the accumulator.
+            const uint8_t* xt = xtile0 + buf * kXTileBytes + sub * kXRowBytes + 16 * g;
+            const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
+            f32x4 blk[RG][TG];
+            f32x4 sc[RG];
+            float lv[2][8];
+            issue_pair_lookups(c[0][0][0], table, lane_off, lv[0]);
+#pragma unroll
+            for (int j = 0; j < kSteps; ++j) {
+                half8_t xb[TG];
+#pragma unroll
+                for (int t = 0; t < TG; ++t)
+                    xb[t] = *(const half8_t*)(xt + t * 16 * kXRowBytes + 256 * (j >> 2) + 64 * (j & 3));
+                if ((j & 1) == 0) {
+#pragma unroll
+                    for (int r = 0; r < RG; ++r)
+                        sc[r] = *(const f32x4*)(wave_scales + r * (kScaleBytes / 4) + (j >> 1) * 16 + 4 * g);
+                }
+#pragma unroll
+                for (int r = 0; r < RG; ++r) {
+                    const int p = j * RG + r;
+                    if (p + 1 < kSteps * RG) {
+                        const int pj = (p + 1) / RG, pr = (p + 1) % RG;
+                        issue_pair_lookups(c[pr][pj >> 2][pj & 3], table, lane_off, lv[(p + 1) & 1]);
+                        lds_wait<4>();
+                    } else {
+                        lds_wait<0>();
+                    }
+                    u32x4 a, a_lo;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        a[i] = __builtin_bit_cast(uint32_t, lv[p & 1][2 * i]);
+                        a_lo[i] = __builtin_bit_cast(uint32_t, lv[p & 1][2 * i + 1]);
+                    }
+                    const half8_t ah = __builtin_bit_cast(half8_t, a), al = __builtin_bit_cast(half8_t, a_lo);
+#pragma unroll
+                    for (int t = 0; t < TG; ++t) {
+                        blk[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ah, xb[t], (j & 1) ? blk[r][t] : zero, 0, 0, 0);
+                        blk[r][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(al, xb[t], blk[r][t], 0, 0, 0);
+                    }
+                    if (j & 1) {
+#pragma unroll
+                        for (int t = 0; t < TG; ++t)
+#pragma unroll
+                            for (int i = 0; i < 4; ++i)
+                                acc[r][t][i] = __builtin_fmaf(sc[r][i], blk[r][t][i], acc[r][t][i]);
+                    }
+                }
+            }
+            store_x(buf ^ 1);
+            __syncthreads();
+            return;
+        }
         // ---- dequantise to FP16 in registers and multiply: lookups pipelined two dwords deep
         const uint8_t* xt = xtile0 + buf * kXTileBytes + sub * kXRowBytes + 64 * g;
-        constexpr int kSteps = 4 * kH;
         float lv[2][8];
         issue_pair_lookups(c[0][0][0], table, lane_off, lv[0]);
 #pragma unroll
@@ -347,22 +430,25 @@ SplitPlan plan_split(int64_t N, int64_t K, int B) {
     return p;
 }
 
-template <int TG, int RG, int W>
+template <int TG, int RG, int W, bool SPLIT = false>
 static void launch_splitk(const SplitPlan& p, const uint8_t* packed, const uint8_t* q8, const float* scale2,
                           const float* offset, const float* code2, int log2_bs, int64_t N, int64_t K,
                           const _Float16* x, int B, float* partial, _Float16* y, hipStream_t s) {
-    hipLaunchKernelGGL((gemm_splitk_kernel<TG, RG, W, window_of(TG)>), dim3((unsigned)p.row_blocks, (unsigned)p.splits),
+    hipLaunchKernelGGL((gemm_splitk_kernel<TG, RG, W, window_of(TG), SPLIT>), dim3((unsigned)p.row_blocks, (unsigned)p.splits),
                        dim3(W * kWave), 0, s, packed, q8, scale2, offset, code2, log2_bs, N, K, x, B, p.wps,
                        p.splits > 1 ? partial : nullptr, y);
 }
 
 int launch_gemm_splitk(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
                        const float* code2, int log2_bs, int64_t N, int64_t K, const _Float16* x, int B,
-                       _Float16* y, float* partial, hipStream_t s) {
+                       _Float16* y, float* partial, bool gemv_weights, hipStream_t s) {
     const SplitPlan p = plan_split(N, K, B);
 #define NF4_SK_ARGS p, packed, q8, scale2, offset, code2, log2_bs, N, K, x, B, partial, y, s
     switch (p.tg) {
-        case 1: launch_splitk<1, 1, 16>(NF4_SK_ARGS); break;
+        case 1:
+            if (gemv_weights) launch_splitk<1, 1, 16, true>(NF4_SK_ARGS);     // at most 16 tokens
+            else launch_splitk<1, 1, 16>(NF4_SK_ARGS);
+            break;
         case 2: launch_splitk<2, 1, 16>(NF4_SK_ARGS); break;
         case 3: launch_splitk<3, 1, 16>(NF4_SK_ARGS); break;
         default: launch_splitk<4, 1, 16>(NF4_SK_ARGS); break;

@@ -516,6 +516,10 @@ namespace nf4 {
 //   28672 x 8192:  3 tokens 44.8 / 54.9,  4 tokens 54.0 / 55.4,  5 tokens 62.3 / 55.4,  6 tokens 76.3 / 56.2
 // (matrices of 16384 rows and more run it with more workgroups than stay resident, which costs it 12 us).
 static int mfma_min_tokens(int64_t N) { return N < 16384 ? 3 : 5; }
+// With a workspace (nf4_dequant_gemv_ws) the matrix-core sum is split along K across workgroups that share the
+// activations through LDS: 38-41 us for 2 to 16 tokens on both 70B MLP shapes, against 36-37 us for the FMA kernels
+// at 2 tokens and 41-44 at 3.
+constexpr int kSplitMinTokens = 3;
 }
 
 extern "C" int nf4_dequant_gemv(const uint8_t* packed, const uint8_t* absmax_q8, const float* scale2,
@@ -545,4 +549,37 @@ extern "C" int nf4_dequant_gemv(const uint8_t* packed, const uint8_t* absmax_q8,
                                 (_Float16*)y, s);
     return gemv_tokens(packed, absmax_q8, scale2, offset, code2, log2_bs, N, K, (const _Float16*)x, B,
                        (_Float16*)y, s);
+}
+
+// ---- the same sum with a caller workspace: from kSplitMinTokens tokens on K is split across workgroups (the
+// split-K kernel of nf4_gemm_splitk.hip with the GEMV's weights: levels as two FP16 terms, FP32 block scales).
+extern "C" size_t nf4_dequant_gemv_workspace_bytes(int64_t N, int64_t K, int B) {
+    if (N <= 0 || K <= 0 || B < 1 || B > 16) return 0;
+    const nf4::SplitPlan p = nf4::plan_split(N, K, B);
+    return p.splits > 1 ? (size_t)p.splits * (size_t)B * (size_t)N * sizeof(float) : 16;
+}
+
+extern "C" int nf4_dequant_gemv_ws(const uint8_t* packed, const uint8_t* absmax_q8, const float* scale2,
+                                   const float* offset, const float* code2, int blocksize, int64_t N, int64_t K,
+                                   const void* x, int B, void* y, void* workspace, size_t workspace_bytes,
+                                   void* stream) {
+    using namespace nf4;
+    if (N < 0 || K < 0) return NF4_ERR_SIZE;
+    const int log2_bs = log2_blocksize(blocksize);
+    if (log2_bs < 0) return NF4_ERR_BLOCKSIZE;
+    if (B < 1 || B > 16) return NF4_ERR_SHAPE;
+    if (N > 0 && (K <= 0 || K % blocksize != 0)) return NF4_ERR_SHAPE;
+    if (N > 0x7fffffffLL) return NF4_ERR_SIZE;
+    if (N == 0) return NF4_OK;
+    if (!packed || !absmax_q8 || !scale2 || !offset || !code2 || !x || !y || !workspace) return NF4_ERR_NULL;
+    if (!aligned(packed, 16) || !aligned(x, 16) || !aligned(y, 2) || !aligned(scale2, 4) || !aligned(offset, 4) ||
+        !aligned(code2, 4) || !aligned(workspace, 16))
+        return NF4_ERR_ALIGN;
+    if (workspace_bytes < nf4_dequant_gemv_workspace_bytes(N, K, B)) return NF4_ERR_SIZE;
+    hipStream_t s = (hipStream_t)stream;
+    if (B < kSplitMinTokens)
+        return gemv_tokens(packed, absmax_q8, scale2, offset, code2, log2_bs, N, K, (const _Float16*)x, B,
+                           (_Float16*)y, s);
+    return launch_gemm_splitk(packed, absmax_q8, scale2, offset, code2, log2_bs, N, K, (const _Float16*)x, B,
+                              (_Float16*)y, (float*)workspace, true, s);
 }

@@ -44,14 +44,16 @@ struct SplitPlan {
 };
 SplitPlan plan_split(int64_t N, int64_t K, int B);
 
-// The GEMV's sum (FP32 weights, here to 22 bits as two FP16 terms) on the matrix cores, B <= 16 (nf4_gemm.hip).
+// The GEMV's sum (FP32 weights: levels to 22 bits as two FP16 terms, FP32 block scales) on the matrix cores,
+// B <= 16 (nf4_gemm.hip).
 int launch_gemv_mfma(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
                      const float* code2, int log2_bs, int64_t N, int64_t K, const _Float16* x, int B, _Float16* y,
                      hipStream_t s);
 
-// Split-K GEMM: `partial` holds plan.splits * B * N floats when plan.splits > 1.
+// Split-K GEMM: `partial` holds plan.splits * B * N floats when plan.splits > 1.  gemv_weights (B <= 16): W is the
+// FP32 product level * scale (levels as two FP16 terms, FP32 block scales) instead of rne_fp16(level * scale).
 int launch_gemm_splitk(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
                        const float* code2, int log2_bs, int64_t N, int64_t K, const _Float16* x, int B,
-                       _Float16* y, float* partial, hipStream_t s);
+                       _Float16* y, float* partial, bool gemv_weights, hipStream_t s);
 
 }  // namespace nf4

@@ -31,6 +31,7 @@ def test_every_declared_symbol_is_exported(L):
     names = declared_functions()
     assert set(names) >= {"nf4_dequantize", "nf4_dequantize_dq", "nf4_dequant_gemv", "nf4_quantize_ref",
                           "nf4_quantize", "nf4_dq_encode", "nf4_dequant_gemm", "nf4_dequant_gemm_workspace_bytes", "nf4_dequantize_batch", "nf4_dequantize_codebook",
+                          "nf4_dequant_gemv_ws", "nf4_dequant_gemv_workspace_bytes",
                           "nf4_dequantize_dq_codebook", "nf4_quantize_ref_codebook", "nf4_last_hip_error", "nf4_status_string"}
     for name in names:
         assert hasattr(L, name), name
@@ -136,6 +137,29 @@ def test_dequantize_batch_argument_checks(L):
     assert call([dq(c2=None)]) == E_NULL
     assert call([dq(s2=P + 1)]) == E_ALIGN
     assert call([fp32(n=0), fp32(), dq()]) == E_SHAPE                      # two kinds of scales in one call
+
+
+def test_gemv_with_workspace_argument_checks(L):
+    f = L.nf4_dequant_gemv_ws
+    a = [P] * 5
+    big = 1 << 40
+    assert f(*a, 64, -1, 64, P, 1, P, P, big, None) == E_SIZE
+    assert f(*a, 48, 4, 64, P, 1, P, P, big, None) == E_BS
+    assert f(*a, 64, 4, 64, P, 0, P, P, big, None) == E_SHAPE
+    assert f(*a, 64, 4, 64, P, 17, P, P, big, None) == E_SHAPE
+    assert f(*a, 64, 4, 96, P, 1, P, P, big, None) == E_SHAPE
+    assert f(*a, 64, 0, 64, P, 1, P, P, big, None) == OK              # no rows: nothing to do
+    assert f(*a, 64, 4, 64, None, 1, P, P, big, None) == E_NULL
+    assert f(*a, 64, 4, 64, P, 1, None, P, big, None) == E_NULL
+    assert f(*a, 64, 4, 64, P, 1, P, None, 0, None) == E_NULL         # the workspace is not optional here
+    assert f(*a, 64, 4, 64, P + 2, 1, P, P, big, None) == E_ALIGN
+    assert f(*a, 64, 4, 64, P, 1, P, P + 4, big, None) == E_ALIGN
+    need = L.nf4_dequant_gemv_workspace_bytes(4096, 8192, 16)
+    assert need >= 2 * 16 * 4096 * 4
+    assert f(*a, 64, 4096, 8192, P, 16, P, P, need - 1, None) == E_SIZE
+    g = L.nf4_dequant_gemv_workspace_bytes
+    assert g(0, 64, 1) == 0 and g(4, 0, 1) == 0 and g(4, 64, 0) == 0 and g(4, 64, 17) == 0
+    assert g(4, 64, 1) > 0
 
 
 def test_gemm_workspace_bytes_of_rejected_shapes_is_zero(L):

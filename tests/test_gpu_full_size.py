@@ -169,20 +169,26 @@ def test_config4_gemv_70b_mlp_shapes(N, K):
         y = torch.full((B, N), float("nan"), dtype=torch.float16, device="cuda")
         nf4.nf4_dequant_gemv(bufs["packed"], bufs["absmax_q8"], bufs["scale2"], bufs["offset"], bufs["code2"], 64,
                              N, K, torch.from_numpy(x).cuda(), B, y)
+        # the same with a workspace (poisoned: every partial sum that is read must have been written)
+        y_ws = torch.full((B, N), float("nan"), dtype=torch.float16, device="cuda")
+        ws = torch.full((nf4.nf4_dequant_gemv_workspace_bytes(N, K, B),), 0xFF, dtype=torch.uint8, device="cuda")
+        nf4.nf4_dequant_gemv_ws(bufs["packed"], bufs["absmax_q8"], bufs["scale2"], bufs["offset"], bufs["code2"],
+                                64, N, K, torch.from_numpy(x).cuda(), B, y_ws, ws)
         torch.cuda.synchronize()
-        yh = y.cpu().numpy().astype(np.float64)
-        assert np.isfinite(yh).all()
         ref = np.empty((B, rows.size))
         for j, r in enumerate(rows):
             _, r64 = oracle.dequant_gemv_rows(host["packed"], host["absmax_q8"], host["scale2"], host["offset"],
                                               host["code2"], N, K, x.view(np.uint16), int(r), 1)
             ref[:, j] = r64[:, 0]
-        got = yh[:, rows]
         rms = np.sqrt(np.mean(ref ** 2))
-        assert np.all(np.abs(got - ref) <= 1e-2 * np.abs(ref) + 1e-2 * rms)
-        rel = np.abs(got - ref).max() / np.abs(ref).max()
-        print(f"gemv N={N} K={K} B={B}: max err / max |y| = {rel:.2e}")
-        assert rel < 2e-3
+        for which, out in (("gemv", y), ("gemv with workspace", y_ws)):
+            yh = out.cpu().numpy().astype(np.float64)
+            assert np.isfinite(yh).all(), which
+            got = yh[:, rows]
+            assert np.all(np.abs(got - ref) <= 1e-2 * np.abs(ref) + 1e-2 * rms), which
+            rel = np.abs(got - ref).max() / np.abs(ref).max()
+            print(f"{which} N={N} K={K} B={B}: max err / max |y| = {rel:.2e}")
+            assert rel < 2e-3, which
 
 
 @pytest.mark.parametrize("N,K", synth.GEMV_SHAPES)

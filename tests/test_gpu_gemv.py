@@ -225,3 +225,77 @@ def test_matrix_core_path_matches_the_fma_path_closely():
     scale = np.abs(ref).max()
     assert np.abs(y_mfma - ref).max() / scale < 1e-3 and np.abs(y_fma - ref).max() / scale < 1e-3
     assert np.abs(y_mfma - y_fma).max() / scale < 1e-3
+
+
+# ---- nf4_dequant_gemv_ws: the same sum with a caller workspace (K split across workgroups from 3 tokens on)
+
+def gemv_ws_gpu(case, N, K, x, poison=True):
+    p, q8, s2, off, c2 = case
+    B = x.shape[0]
+    y = torch.full((B, N), float("nan"), dtype=torch.float16, device="cuda")
+    ws = torch.empty(nf4.nf4_dequant_gemv_workspace_bytes(N, K, B), dtype=torch.uint8, device="cuda")
+    if poison:
+        ws.fill_(0xFF)                                   # NaN patterns: every partial sum read must have been written
+    nf4.nf4_dequant_gemv_ws(dev(p), dev(q8), dev(s2), dev(off), dev(c2), 64, N, K, dev(x), B, y, ws)
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+@pytest.mark.parametrize("B", [1, 2, 3, 4, 7, 11, 16])
+@pytest.mark.parametrize("N,K", [(37, 256), (64, 2048 + 512), (9, 8192), (130, 64), (300, 4096 + 64), (41, 18496)])
+def test_workspace_form_small_shapes_all_batches(N, K, B):
+    """Ragged rows (N not a multiple of 16 or 256), K from one block to many windows with a ragged last window,
+    every token count: against the oracle, to the GEMV's bar."""
+    case = make_case(N, K, seed=N * 5 + K)
+    x = synth.activations_fp16(B, K, seed=B + 31)
+    _, ref = oracle.dequant_gemv(*case, N, K, x.view(np.uint16))
+    y = gemv_ws_gpu(case, N, K, x)
+    assert np.isfinite(y).all()
+    assert within_bar(y, ref)
+    assert np.abs(y - ref).max() / np.abs(ref).max() < 2e-3
+
+
+def test_workspace_form_one_and_two_tokens_equal_the_plain_call():
+    """Below three tokens the workspace is not used: the same kernels, bit-identical results."""
+    N, K = 48, 4096
+    case = make_case(N, K, seed=77)
+    for B in (1, 2):
+        x = synth.activations_fp16(B, K, seed=B)
+        assert np.array_equal(gemv_ws_gpu(case, N, K, x).view(np.uint16), gemv_gpu(case, N, K, x).view(np.uint16))
+
+
+def test_workspace_form_carries_the_weight_to_22_bits_and_is_deterministic():
+    """Unit vectors pick single weights: rne_fp16(W (1 + e)), |e| <= 2^-21, as on the matrix-core path without a
+    workspace; and two calls give the same bits (the partial sums are added in a fixed order)."""
+    N, K = 272, 6144                                     # two row blocks of 256 rows, several splits of K
+    case = make_case(N, K, seed=23)
+    w = oracle.dequantize_dq(*case, N * K, out_dtype=oracle.FP32).reshape(N, K)
+    ks = [0, 1, 7, 8, 31, 32, 63, 64, 127, 511, 512, 1023, 4095, 4096, K - 65, K - 1]
+    x = np.zeros((len(ks), K), np.float16)
+    for b, k in enumerate(ks):
+        x[b, k] = 1.0
+    y = gemv_ws_gpu(case, N, K, x)
+    want = w[:, ks].T
+    ulp = np.spacing(np.abs(want).astype(np.float16)).astype(np.float64)
+    err = np.abs(y.astype(np.float64) - want.astype(np.float64))
+    assert np.all(err <= 0.5 * ulp + np.abs(want) * 2.0 ** -21 + 2.0 ** -24)
+    assert np.mean(y.view(np.uint16) == want.astype(np.float16).view(np.uint16)) > 0.99
+    xr = synth.activations_fp16(16, K, seed=5)
+    y1, y2 = gemv_ws_gpu(case, N, K, xr), gemv_ws_gpu(case, N, K, xr, poison=False)
+    assert np.array_equal(y1.view(np.uint16), y2.view(np.uint16))
+
+
+def test_workspace_form_with_huge_and_tiny_scales():
+    """The block scale stays FP32 on the matrix-core paths, so weights beyond the FP16 range and scales far below it
+    are carried like any other (y itself must still fit FP16: the activations are scaled to keep it there)."""
+    N, K = 32, 1024
+    p = synth.random_codes(N * K // 2, seed=9)
+    q8 = np.full(N * K // 64, 254, np.uint8)
+    c2 = ((np.arange(256) - 127) / 127).astype(np.float32)
+    for scale, xmag in ((3.0e5, 1.0e-4), (1.0e-9, 1.0e4)):
+        case = (p, q8, np.full(N * K // 64 // 256, scale, np.float32), np.zeros(1, np.float32), c2)
+        x = (synth.activations_fp16(5, K, seed=3).astype(np.float32) * xmag).astype(np.float16)
+        _, ref = oracle.dequant_gemv(*case, N, K, x.view(np.uint16))
+        for y in (gemv_ws_gpu(case, N, K, x), gemv_gpu(case, N, K, x)):
+            assert np.isfinite(y).all()
+            assert np.abs(y - ref).max() / np.abs(ref).max() < 2e-3

@@ -39,7 +39,9 @@ def test_captured_calls_replay_bit_exactly():
     outcb = torch.empty(n, dtype=torch.bfloat16, device="cuda")
     b1 = torch.empty(n, dtype=torch.float16, device="cuda")            # one launch for two tensors
     b2 = torch.empty(5000, dtype=torch.float16, device="cuda")
-    outputs = [out16, outbf, yv, ym, qp, qa, ys, outcb, b1, b2]
+    yw = torch.empty((8, N), dtype=torch.float16, device="cuda")           # GEMV with a workspace: two kernels per call
+    wsv = torch.empty(nf4.nf4_dequant_gemv_workspace_bytes(N, K, 8), dtype=torch.uint8, device="cuda")
+    outputs = [out16, outbf, yv, ym, qp, qa, ys, outcb, b1, b2, yw]
 
     def run(stream):
         nf4.nf4_dequantize(d["p"], d["a"], 64, n, out16, stream=stream)
@@ -50,6 +52,8 @@ def test_captured_calls_replay_bit_exactly():
         nf4.nf4_dequant_gemm(d["pm"], d["mq8"], d["ms2"], d["moff"], d["mc2"], 64, N, K, d["x"], B, ys, workspace=ws,
                              stream=stream)
         nf4.nf4_dequantize_dq_codebook(d["p"], d["q8"], d["s2"], d["off"], d["c2"], 256, cb, 64, n, outcb, stream=stream)
+        nf4.nf4_dequant_gemv_ws(d["pm"], d["mq8"], d["ms2"], d["moff"], d["mc2"], 64, N, K, d["x"], 8, yw, wsv,
+                                stream=stream)
         nf4.nf4_dequantize_batch([dict(packed=d["p"], absmax=d["a"], out=b1, n=n),
                                   dict(packed=d["p"], absmax=d["a"], out=b2, n=5000)], 64, stream=stream)
 
@@ -63,7 +67,7 @@ def test_captured_calls_replay_bit_exactly():
     with torch.cuda.graph(graph, stream=side):
         run(torch.cuda.current_stream())
     for replay in range(4):
-        for t in outputs + [ws]:                           # eager work between replays: poison outputs and workspace
+        for t in outputs + [ws, wsv]:                      # eager work between replays: poison outputs and workspaces
             t.view(torch.uint8).fill_(0xA5)
         torch.cuda.synchronize()
         graph.replay()

@@ -161,7 +161,7 @@ def test_quantize_more_than_2_pow_32_elements(tuned):
 @pytest.mark.parametrize("B", [1, 4, 16])
 def test_gemv_and_gemm_on_a_matrix_of_more_than_2_pow_32_weights(B):
     """N x K > 2^32: sampled rows (first, last, and those whose flat index crosses 2^31 and 2^32) against the
-    oracle, for the GEMV and for both algorithms of the GEMM."""
+    oracle, for the GEMV with and without a workspace and for both algorithms of the GEMM."""
     N, K = 32768 + 48, 131072 + 64
     n = N * K
     assert n > (1 << 32)
@@ -180,8 +180,11 @@ def test_gemv_and_gemm_on_a_matrix_of_more_than_2_pow_32_weights(B):
     nf4.nf4_dequant_gemv(packed, q8, scale2, offset, code2, 64, N, K, x, B, yv)
     nf4.nf4_dequant_gemm(packed, q8, scale2, offset, code2, 64, N, K, x, B, ym)
     nf4.nf4_dequant_gemm(packed, q8, scale2, offset, code2, 64, N, K, x, B, ys, workspace=ws)
+    yw = torch.full((B, N), float("nan"), dtype=torch.float16, device="cuda")
+    wsv = torch.empty(nf4.nf4_dequant_gemv_workspace_bytes(N, K, B), dtype=torch.uint8, device="cuda")
+    nf4.nf4_dequant_gemv_ws(packed, q8, scale2, offset, code2, 64, N, K, x, B, yw, wsv)
     torch.cuda.synchronize()
-    for y in (yv, ym, ys):
+    for y in (yv, ym, ys, yw):
         assert not bool(torch.isnan(y).any().item())
 
     hp, hq, hs = packed.cpu().numpy(), q8.cpu().numpy(), scale2.cpu().numpy()
@@ -192,6 +195,7 @@ def test_gemv_and_gemm_on_a_matrix_of_more_than_2_pow_32_weights(B):
         _, ref_v = oracle.dequant_gemv_rows(hp, hq, hs, ho, hc, N, K, hx, r0, cnt)
         _, ref_m = oracle.dequant_gemm_rows(hp, hq, hs, ho, hc, N, K, hx, r0, cnt)
         rms = max(float(np.sqrt(np.mean(ref_v ** 2))), 1e-6)
-        for y, ref, what in ((yv, ref_v, "gemv"), (ym, ref_m, "gemm"), (ys, ref_m, "gemm split-K")):
+        for y, ref, what in ((yv, ref_v, "gemv"), (yw, ref_v, "gemv with workspace"), (ym, ref_m, "gemm"),
+                             (ys, ref_m, "gemm split-K")):
             got = y[:, r0:r0 + cnt].cpu().numpy().astype(np.float64)
             assert np.all(np.abs(got - ref) <= 1e-2 * np.abs(ref) + 1e-2 * rms), (what, r0)

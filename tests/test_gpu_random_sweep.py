@@ -132,11 +132,16 @@ def test_random_long_rows_gemv_and_both_gemm_algorithms():
         dp, dq8, ds2, doff, dc2 = dev(p), dev(q8), dev(s2), dev(off), dev(c2)
         rows = np.unique(np.concatenate([[0, N - 1], rng.integers(0, N, 6)]))      # oracle on sampled rows
         for B, which in ((int(rng.integers(1, 7)), "gemv"), (int(rng.integers(7, 17)), "gemv"),
+                         (int(rng.integers(3, 17)), "gemv with workspace"),
                          (int(rng.integers(1, 65)), "gemm"), (int(rng.integers(1, 65)), "gemm split")):
             x = synth.activations_fp16(B, K, seed=70_000 + case)
             y = torch.full((B, N), float("nan"), dtype=torch.float16, device="cuda")
             if which == "gemv":
                 nf4.nf4_dequant_gemv(dp, dq8, ds2, doff, dc2, 64, N, K, dev(x), B, y)
+                ofn = oracle.dequant_gemv_rows
+            elif which == "gemv with workspace":
+                ws = torch.full((nf4.nf4_dequant_gemv_workspace_bytes(N, K, B),), 0xFF, dtype=torch.uint8, device="cuda")
+                nf4.nf4_dequant_gemv_ws(dp, dq8, ds2, doff, dc2, 64, N, K, dev(x), B, y, ws)
                 ofn = oracle.dequant_gemv_rows
             else:
                 ws = None
