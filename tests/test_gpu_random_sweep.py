@@ -106,7 +106,13 @@ def test_random_gemv_and_gemm_cases():
         w = synth.gaussian_weights(N * K, 0.015, seed=40_000 + case)
         p, a = oracle.quantize(w, bs)
         q8, s2, off, c2 = oracle.dq_encode(a)
+        def gemv_with_workspace(*args):                   # the same call plus a poisoned workspace
+            B = args[9]
+            ws = torch.full((nf4.nf4_dequant_gemv_workspace_bytes(N, K, B),), 0xFF, dtype=torch.uint8, device="cuda")
+            return nf4.nf4_dequant_gemv_ws(*args, ws)
+
         for B, fn, ofn in ((int(rng.integers(1, 17)), nf4.nf4_dequant_gemv, oracle.dequant_gemv_rows),
+                           (int(rng.integers(3, 17)), gemv_with_workspace, oracle.dequant_gemv_rows),
                            (int(rng.integers(1, 65)), nf4.nf4_dequant_gemm, oracle.dequant_gemm_rows)):
             x = synth.activations_fp16(B, K, seed=50_000 + case)
             _, ref = ofn(p, q8, s2, off, c2, N, K, x.view(np.uint16), 0, N, blocksize=bs)
