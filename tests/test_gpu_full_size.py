@@ -1,14 +1,17 @@
 """GPU parity at the full sizes of the benchmark configurations, in the launch
 configuration bench.py times (same entry points, same argument shapes).
 
-The tensors are too large for an element-by-element oracle pass, so each test
-draws the weights on the GPU from a seeded generator, quantises them with
-nf4_quantize_ref, dequantises, and then (a) recomputes a random sample of
-quantisation blocks (plus the first and last ones) with the CPU oracle --
-both the quantiser's codes/scales and the dequantised values, bit for bit --
-and (b) checks a property that holds for every block of any tensor: a block's
-largest dequantised magnitude is its scale rounded to the output type (code 0
-or 15 is always present in a quantised block)."""
+Each test draws the weights on the GPU from a seeded generator, quantises them
+with nf4_quantize_ref and dequantises.  The dequantised tensor is then compared
+with the CPU oracle over EVERY element, bit for bit (the oracle's plain loop,
+split on block boundaries over the host threads, takes a fraction of a second
+per tensor); the quantiser's codes and scales are recomputed by the oracle on a
+random sample of blocks (plus the first and last ones), since its 16-way search
+per element is too slow for 10^8 elements; and one property is checked on every
+block: a block's largest dequantised magnitude is its scale rounded to the
+output type (code 0 or 15 is always present in a quantised block).  The fused
+GEMV is compared with the oracle's double-precision sums over every output of
+both 70B MLP shapes at 1 and 16 tokens, and on sampled rows at 4 tokens."""
 import numpy as np
 import pytest
 import torch
@@ -16,6 +19,7 @@ import torch
 import oracle
 from paper_2604_02556_amd import binding as nf4
 from paper_2604_02556_amd import synth
+from gpu_util import oracle_dequantize_threaded, oracle_rows_threaded
 
 pytestmark = pytest.mark.gpu
 
@@ -42,20 +46,25 @@ def bits16(t):
     return t.view(torch.int16).cpu().numpy().view(np.uint16)
 
 
-def check_sampled(w, bufs, out, idx, odt, absmax_host=None):
-    """Oracle on the sampled blocks: quantiser parity and dequantiser parity."""
+def check_quantizer_sampled(w, bufs, idx):
+    """Oracle quantiser on the sampled blocks: codes and scales bit for bit."""
     ti = torch.from_numpy(idx).cuda()
     src = w.view(-1, 64)[ti].cpu().numpy().reshape(-1)
     pk = bufs["packed"].view(-1, 32)[ti].cpu().numpy().reshape(-1)
     am = bufs["absmax"][ti].cpu().numpy()
-    got = bits16(out.view(torch.int16).view(-1, 64)[ti]).reshape(-1)
     op, oa = oracle.quantize(src)
     assert np.array_equal(oa, am), "quantize_ref absmax differs from the oracle on sampled blocks"
     assert np.array_equal(op, pk), "quantize_ref codes differ from the oracle on sampled blocks"
-    scales = am if absmax_host is None else absmax_host[idx]
-    want = oracle.dequantize(pk, scales, src.size, out_dtype=odt)
-    bad = int((got != want).sum())
-    assert bad == 0, f"{bad} of {want.size} sampled elements differ"
+
+
+def check_every_element(bufs, out, n, odt, scales_host=None):
+    """The whole dequantised tensor against the oracle, element by element."""
+    packed = bufs["packed"].cpu().numpy()
+    scales = bufs["absmax"].cpu().numpy() if scales_host is None else scales_host
+    want = oracle_dequantize_threaded(packed, scales, n, out_dtype=odt)
+    got = bits16(out[:n])
+    bad = int(np.count_nonzero(got != want))
+    assert bad == 0, f"{bad} of {n} elements differ from the oracle"
 
 
 def check_block_extremes(out, scales_dev, tdt):
@@ -74,7 +83,8 @@ def test_config1_qwen3_32b_shapes_fp16(name):
     out = torch.empty(n, dtype=torch.float16, device="cuda")
     nf4.nf4_dequantize(bufs["packed"], bufs["absmax"], 64, n, out)
     torch.cuda.synchronize()
-    check_sampled(w, bufs, out, sample_blocks(n // 64, n % 1009), oracle.FP16)
+    check_quantizer_sampled(w, bufs, sample_blocks(n // 64, n % 1009))
+    check_every_element(bufs, out, n, oracle.FP16)
     check_block_extremes(out, bufs["absmax"], torch.float16)
 
 
@@ -97,7 +107,8 @@ def test_config2_gemma_27b_shapes_double_quant_bf16(name):
     assert bufs["offset"].cpu().numpy()[0] == off[0]
     assert np.array_equal(bufs["code2"].cpu().numpy(), c2)
     decoded = oracle.dq_decode(q8, s2, off, c2)
-    check_sampled(w, bufs, out, sample_blocks(n // 64, n % 1013), oracle.BF16, absmax_host=decoded)
+    check_quantizer_sampled(w, bufs, sample_blocks(n // 64, n % 1013))
+    check_every_element(bufs, out, n, oracle.BF16, scales_host=decoded)
     check_block_extremes(out, torch.from_numpy(decoded).cuda(), torch.bfloat16)
 
 
@@ -117,12 +128,12 @@ def test_config3_llama33_70b_layer_streamed_into_one_buffer():
         nf4.nf4_dequantize(bufs["packed"], bufs["absmax"], 64, n, out, stream=stream)
         stream.synchronize()
         view = out[:n]
-        if name in ("k", "v"):                             # small enough for a full oracle pass
+        if name in ("k", "v"):                             # small enough for the oracle's quantiser on every block
             p, a = oracle.quantize(w.cpu().numpy())
             assert np.array_equal(bufs["packed"].cpu().numpy(), p) and np.array_equal(bufs["absmax"].cpu().numpy(), a)
-            assert np.array_equal(bits16(view), oracle.dequantize(p, a, n))
         else:
-            check_sampled(w, bufs, view, sample_blocks(n // 64, 3000 + ti), oracle.FP16)
+            check_quantizer_sampled(w, bufs, sample_blocks(n // 64, 3000 + ti))
+        check_every_element(bufs, view, n, oracle.FP16)
         check_block_extremes(view, bufs["absmax"], torch.float16)
 
 
@@ -155,6 +166,12 @@ def test_config3_llama33_70b_layer_in_one_launch():
 
 @pytest.mark.parametrize("N,K", synth.GEMV_SHAPES)
 def test_config4_gemv_70b_mlp_shapes(N, K):
+    """Both 70B MLP shapes at 1, 4 and 16 tokens, with and without a workspace.  At 1 and 16 tokens EVERY output is
+    compared with the oracle's double-precision sum (all N rows, on the host threads); at 4 tokens 32 sampled
+    rows.  Bar: |y - ref| <= 1e-2 |ref| + 1e-2 rms(ref) per output (a purely relative bound is undefined where the
+    reference sum passes through zero); reported and asserted besides: the largest error relative to the largest
+    |ref| (< 2e-3), and the largest purely relative error over the outputs with |ref| >= rms (< 1e-2, the stated
+    bar without the rms term where it is meaningful)."""
     n = N * K
     w = draw(n, synth.LLAMA33_70B_SIGMA, 4000 + N % 7)
     bufs = nf4.alloc_quantized(n, dq=True)
@@ -163,7 +180,7 @@ def test_config4_gemv_70b_mlp_shapes(N, K):
     torch.cuda.synchronize()
     host = {k: v.cpu().numpy() for k, v in bufs.items()}
     rng = np.random.Generator(np.random.PCG64(N + K))
-    rows = np.unique(np.concatenate([np.arange(5), np.arange(N - 5, N), rng.integers(0, N, 22)]))
+    sampled = np.unique(np.concatenate([np.arange(5), np.arange(N - 5, N), rng.integers(0, N, 22)]))
     for B in synth.GEMV_BATCHES:
         x = synth.activations_fp16(B, K, seed=4100 + B)
         y = torch.full((B, N), float("nan"), dtype=torch.float16, device="cuda")
@@ -175,20 +192,29 @@ def test_config4_gemv_70b_mlp_shapes(N, K):
         nf4.nf4_dequant_gemv_ws(bufs["packed"], bufs["absmax_q8"], bufs["scale2"], bufs["offset"], bufs["code2"],
                                 64, N, K, torch.from_numpy(x).cuda(), B, y_ws, ws)
         torch.cuda.synchronize()
-        ref = np.empty((B, rows.size))
-        for j, r in enumerate(rows):
-            _, r64 = oracle.dequant_gemv_rows(host["packed"], host["absmax_q8"], host["scale2"], host["offset"],
-                                              host["code2"], N, K, x.view(np.uint16), int(r), 1)
-            ref[:, j] = r64[:, 0]
+        if B in (1, 16):
+            rows = np.arange(N)
+            ref = oracle_rows_threaded(oracle.dequant_gemv_rows, host, N, K, x.view(np.uint16))
+        else:
+            rows = sampled
+            ref = np.empty((B, rows.size))
+            for j, r in enumerate(rows):
+                _, r64 = oracle.dequant_gemv_rows(host["packed"], host["absmax_q8"], host["scale2"], host["offset"],
+                                                  host["code2"], N, K, x.view(np.uint16), int(r), 1)
+                ref[:, j] = r64[:, 0]
         rms = np.sqrt(np.mean(ref ** 2))
+        big = np.abs(ref) >= rms
         for which, out in (("gemv", y), ("gemv with workspace", y_ws)):
             yh = out.cpu().numpy().astype(np.float64)
             assert np.isfinite(yh).all(), which
-            got = yh[:, rows]
-            assert np.all(np.abs(got - ref) <= 1e-2 * np.abs(ref) + 1e-2 * rms), which
-            rel = np.abs(got - ref).max() / np.abs(ref).max()
-            print(f"{which} N={N} K={K} B={B}: max err / max |y| = {rel:.2e}")
+            err = np.abs(yh[:, rows] - ref)
+            assert np.all(err <= 1e-2 * np.abs(ref) + 1e-2 * rms), which
+            rel = err.max() / np.abs(ref).max()
+            rel_big = (err[big] / np.abs(ref[big])).max()
+            print(f"{which} N={N} K={K} B={B} rows={rows.size}: max err / max |y| = {rel:.2e}, "
+                  f"max relative err where |y| >= rms = {rel_big:.2e}")
             assert rel < 2e-3, which
+            assert rel_big < 1e-2, which
 
 
 @pytest.mark.parametrize("N,K", synth.GEMV_SHAPES)
