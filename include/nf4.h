@@ -149,6 +149,29 @@ int nf4_dequant_gemv_ws(const uint8_t* packed, const uint8_t* absmax_q8, const f
 size_t nf4_dequant_gemv_workspace_bytes(int64_t N, int64_t K, int B);
 
 /*
+ * nf4_dequant_gemv_ws for callers that cannot allocate device memory: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * definition of y, same arguments, layouts, limits and results as
+ * nf4_dequant_gemv_ws (bit for bit), without the workspace: the FP32 partial
+ * sums go to a device array of NF4_STATIC_SCRATCH_BYTES that is part of the
+ * library's code object (every GPU the library runs on holds its own copy until
+ * the process ends).  The call allocates and frees nothing.  A shape whose
+ * partial sums do not fit (nf4_dequant_gemv_workspace_bytes(N, K, B) >
+ * NF4_STATIC_SCRATCH_BYTES) returns NF4_ERR_SIZE and launches nothing; K is
+ * split at most as many ways as fill the compute units once, so on a GPU with up
+ * to 256 of them (MI355X) every shape the call accepts needs at most 256 * 256
+ * rows x 16 tokens x 4 bytes = 4 MiB and fits.  All
+ * calls on one GPU share that GPU's array: calls that may overlap on one GPU
+ * (different streams, different threads) race and must be serialised by the
+ * caller.  The first call on a device looks the array's address up
+ * (hipGetSymbolAddress); make that call outside a graph capture.
+ */
+#define NF4_STATIC_SCRATCH_BYTES ((size_t)4 << 20)
+int nf4_dequant_gemv_static(const uint8_t* packed, const uint8_t* absmax_q8, const float* scale2,
+                            const float* offset, const float* code2, int blocksize, int64_t N,
+                            int64_t K, const void* x, int B, void* y, void* stream);
+
+/*
  * Fused dequantise + small-batch GEMM on the matrix cores, for the paper's batch
  * range (Sec. VI-A: 2 to 64).  It is the paper's quantised matmul (Sec. III-A,
  * III-C: dequantise W to FP16, then an FP16 matmul with FP32 accumulation)

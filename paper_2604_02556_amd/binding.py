@@ -55,6 +55,8 @@ def lib():
     L.nf4_dequant_gemv_ws.argtypes = [vp, vp, vp, vp, vp, i32, i64, i64, vp, i32, vp, vp, c.c_size_t, vp]
     L.nf4_dequant_gemv_ws.restype = i32
     L.nf4_dequant_gemv_workspace_bytes.argtypes = [i64, i64, i32]
+    L.nf4_dequant_gemv_static.argtypes = [vp, vp, vp, vp, vp, i32, i64, i64, vp, i32, vp, vp]
+    L.nf4_dequant_gemv_static.restype = i32
     L.nf4_dequant_gemv_workspace_bytes.restype = c.c_size_t
     L.nf4_quantize_ref.argtypes = [vp, i64, i32, vp, vp, vp, vp, vp, vp, vp]
     L.nf4_dequantize_codebook.argtypes = [vp, vp, vp, i32, i64, vp, i32, vp]
@@ -167,6 +169,13 @@ def nf4_dequant_gemv_ws(packed, absmax_q8, scale2, offset, code2, blocksize, N, 
     _check(lib().nf4_dequant_gemv_ws(_ptr(packed), _ptr(absmax_q8), _ptr(scale2), _ptr(offset), _ptr(code2),
                                      blocksize, N, K, _ptr(x), B, _ptr(y), _ptr(workspace), ws_bytes,
                                      _stream(stream)))
+    return y
+
+
+def nf4_dequant_gemv_static(packed, absmax_q8, scale2, offset, code2, blocksize, N, K, x, B, y, stream=None):
+    """nf4_dequant_gemv_ws over the library's own static scratch array: allocates nothing."""
+    _check(lib().nf4_dequant_gemv_static(_ptr(packed), _ptr(absmax_q8), _ptr(scale2), _ptr(offset), _ptr(code2),
+                                         blocksize, N, K, _ptr(x), B, _ptr(y), _stream(stream)))
     return y
 
 

@@ -520,6 +520,13 @@ static int mfma_min_tokens(int64_t N) { return N < 16384 ? 3 : 5; }
 // activations through LDS: 38-41 us for 2 to 16 tokens on both 70B MLP shapes, against 36-37 us for the FMA kernels
 // at 2 tokens and 41-44 at 3.
 constexpr int kSplitMinTokens = 3;
+
+int launch_gemv_ws(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
+                   const float* code2, int log2_bs, int64_t N, int64_t K, const _Float16* x, int B, _Float16* y,
+                   float* partial, hipStream_t s) {
+    if (B < kSplitMinTokens) return gemv_tokens(packed, q8, scale2, offset, code2, log2_bs, N, K, x, B, y, s);
+    return launch_gemm_splitk(packed, q8, scale2, offset, code2, log2_bs, N, K, x, B, y, partial, true, s);
+}
 }
 
 extern "C" int nf4_dequant_gemv(const uint8_t* packed, const uint8_t* absmax_q8, const float* scale2,
@@ -576,10 +583,6 @@ extern "C" int nf4_dequant_gemv_ws(const uint8_t* packed, const uint8_t* absmax_
         !aligned(code2, 4) || !aligned(workspace, 16))
         return NF4_ERR_ALIGN;
     if (workspace_bytes < nf4_dequant_gemv_workspace_bytes(N, K, B)) return NF4_ERR_SIZE;
-    hipStream_t s = (hipStream_t)stream;
-    if (B < kSplitMinTokens)
-        return gemv_tokens(packed, absmax_q8, scale2, offset, code2, log2_bs, N, K, (const _Float16*)x, B,
-                           (_Float16*)y, s);
-    return launch_gemm_splitk(packed, absmax_q8, scale2, offset, code2, log2_bs, N, K, (const _Float16*)x, B,
-                              (_Float16*)y, (float*)workspace, true, s);
+    return launch_gemv_ws(packed, absmax_q8, scale2, offset, code2, log2_bs, N, K, (const _Float16*)x, B,
+                          (_Float16*)y, (float*)workspace, (hipStream_t)stream);
 }
