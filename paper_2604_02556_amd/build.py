@@ -15,8 +15,12 @@ SOURCES = ["nf4_api.hip", "nf4_dequant.hip", "nf4_gemv.hip", "nf4_quantize_ref.h
 # -ffp-contract=off: every FP32 multiply and add is rounded on its own, as the
 # format's definition states (FMAs are written explicitly where wanted).
 # -packed-fp32-ops is switched off: the kernels use scalar FP32 instructions only.
+# -amdgpu-kernarg-preload-count: the first kernel arguments (up to 14 dwords) arrive in the wave's initial scalar
+# registers instead of through a scalar load that every wave waits for before its first memory request; firmware
+# without the feature runs the compatibility prologue the compiler emits, which loads them as before.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-ffp-contract=off", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-mllvm", "-amdgpu-kernarg-preload-count=14",
          "-Wall", "-Wno-unused-command-line-argument"]
 
 

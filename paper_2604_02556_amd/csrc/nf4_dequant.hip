@@ -41,6 +41,24 @@
 //   * whatever does not fill a tile (Sec. V-A: ragged sizes) is handled by one
 //     extra workgroup, a byte (two elements) per lane, every access predicated
 //     on n, so the bulk path carries no bounds checks.
+//   * the size of the output picks the cache policy of the stores and the order
+//     of the two loads (OutClass below), measured on the 70B-shaped stream, in which
+//     every tensor is written into the same reused buffer:
+//       - up to 40 MB of output (it fits the eight 4 MB L2s with room to spare):
+//         non-temporal stores, codes requested before the scales;
+//       - up to 240 MB (it fits the 256 MB memory-side cache): stores at agent
+//         scope without the non-temporal hint (`sc1`).  The output then stays in
+//         that cache, where the next tensor overwrites it and a consumer would find
+//         it: 26.1 instead of 28.4 us for 8192 x 8192;
+//       - above that: `sc1 nt`, and the wave asks for its codes only once its
+//         scales have arrived.  One vector load in flight per wave instead of two
+//         is worth 2.4 % there (91.2 instead of 93.4 us for 8192 x 28672), but only
+//         together with that store policy; with plain non-temporal stores it is
+//         worth nothing, and on the smaller classes it costs 1-2 %;
+//   * the kernel's arguments are plain scalars with the ones a wave needs first in
+//     front, so that they arrive in the wave's initial scalar registers (kernel-
+//     argument preloading, -amdgpu-kernarg-preload-count) instead of through a
+//     scalar load that every wave of a launch waits for: 0.25 us per launch.
 #include "nf4_device.hpp"
 #include "nf4_host.hpp"
 
@@ -58,6 +76,27 @@ struct ScaleArgs {
     int log2_group;          // blocks per second-level scale (8 = the format's 256)
     const float* codebook;   // 16 levels in memory, or nullptr for the NF4 literals
 };
+
+// Memory policy by size of the output (see the head of this file).
+enum OutClass { kOutSmall = 0, kOutCached = 1, kOutStream = 2 };
+constexpr int64_t kCachedMinBytes = int64_t(40) << 20;    // beyond the L2s
+constexpr int64_t kCachedMaxBytes = int64_t(240) << 20;   // inside the 256 MB memory-side cache
+inline OutClass out_class(int64_t n) {
+    const int64_t bytes = 2 * n;
+    return bytes < kCachedMinBytes ? kOutSmall : bytes <= kCachedMaxBytes ? kOutCached : kOutStream;
+}
+
+// 16 bytes to p with the class's cache policy.  The agent-scope forms have no C spelling; the s_nop covers the
+// one wait state a store of more than 8 bytes needs before its data registers may be overwritten, which the
+// compiler cannot see to insert after an asm statement.
+template <int CLS>
+__device__ __forceinline__ void store16(u32x4 v, u32x4* p) {
+    if constexpr (CLS == kOutSmall) __builtin_nontemporal_store(v, p);
+    else if constexpr (CLS == kOutCached)
+        asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 0" ::"v"(p), "v"(v) : "memory");
+    else
+        asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 0" ::"v"(p), "v"(v) : "memory");
+}
 
 // Eight codes of one dword -> eight scaled 16-bit values.  Byte j of the dword
 // holds element 2j in its high nibble and element 2j+1 in its low nibble.
@@ -81,12 +120,11 @@ __device__ __forceinline__ float dq_scale(const ScaleArgs& a, float offset, int6
 }
 
 // The work of one single-wave workgroup: tile `t` of a tensor with `tiles` full tiles, or (t == tiles) its
-// ragged end.
-template <int DT, bool DQ>
+// ragged end.  stage (1 KiB) and lut (16 levels) are the workgroup's LDS.
+template <int DT, bool DQ, int CLS>
 __device__ __forceinline__ void dequant_group(const uint8_t* __restrict__ packed, const ScaleArgs& sa, int log2_bs,
-                                              int64_t n, int64_t tiles, uint16_t* __restrict__ out, int64_t t) {
-    __shared__ uint32_t stage[kTileBytes / 4];
-    __shared__ float lut[16];
+                                              int64_t n, int64_t tiles, uint16_t* __restrict__ out, int64_t t,
+                                              uint32_t* stage, float* lut) {
     const int lane = threadIdx.x;
     const float offset = DQ ? sa.offset[0] : 0.0f;
     // the table: instruction literals for NF4, 64 bytes from memory for a caller's codebook (Sec. V-A: the
@@ -95,7 +133,10 @@ __device__ __forceinline__ void dequant_group(const uint8_t* __restrict__ packed
 
     if (t < tiles) {
         const int64_t e0 = t * kTileElems;
-        const u32x4 codes = *(const u32x4*)(packed + t * kTileBytes + lane * 16);
+        const uint8_t* tile_codes = packed + t * kTileBytes;
+        uint32_t code_off = (uint32_t)lane * 16u;
+        u32x4 codes;
+        if constexpr (CLS == kOutSmall) codes = *(const u32x4*)(tile_codes + code_off);
         // Scales.  Lane l's k-th store covers elements e0 + 512 k + 8 l .. + 7,
         // all inside one quantisation block (blocksize >= 64).
         float s[4];
@@ -106,6 +147,10 @@ __device__ __forceinline__ void dequant_group(const uint8_t* __restrict__ packed
             const int64_t b0 = e0 >> log2_bs;
             float mine = 0.0f;
             if (lane < per_tile) mine = DQ ? dq_scale(sa, offset, b0 + lane) : sa.absmax[b0 + lane];
+            // the largest tensors: the address of the codes is made to depend on the scale, so that the wave
+            // requests its codes only when its scales are there
+            if constexpr (CLS == kOutStream) asm volatile("" : "+v"(code_off) : "v"(mine));
+            if constexpr (CLS != kOutSmall) codes = *(const u32x4*)(tile_codes + code_off);
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const int src = log2_bs >= 11 ? 0 : ((512 * k + 8 * lane) >> log2_bs);
@@ -120,7 +165,7 @@ __device__ __forceinline__ void dequant_group(const uint8_t* __restrict__ packed
         for (int k = 0; k < 4; ++k) {
             const uint32_t q = stage[64 * k + lane];
             const u32x4 v = expand8<DT>(q, s[k], lut);
-            __builtin_nontemporal_store(v, (u32x4*)(out_tile + 512 * k + 8 * lane));
+            store16<CLS>(v, (u32x4*)(out_tile + 512 * k + 8 * lane));
         }
     } else {
         // Ragged end: everything after the last full tile, one byte (two
@@ -147,11 +192,34 @@ __device__ __forceinline__ void dequant_group(const uint8_t* __restrict__ packed
     }
 }
 
-template <int DT, bool DQ>
-__global__ __launch_bounds__(kWave) void dequant_kernel(const uint8_t* __restrict__ packed, ScaleArgs sa,
-                                                        int log2_bs, int64_t n, int64_t tiles,
-                                                        uint16_t* __restrict__ out) {
-    dequant_group<DT, DQ>(packed, sa, log2_bs, n, tiles, out, blockIdx.x);
+// The arguments are plain scalars, the ones a wave needs first in front, so that they travel in the wave's
+// initial scalar registers (kernel-argument preloading) instead of being fetched from memory by every wave before
+// it can issue its first load: packed, the scale pointers, out, tiles and the shifts are 13 or 14 dwords.  `n`
+// (only the ragged end reads it) and the caller's codebook (only read when `shifts` says there is one) come last.
+// shifts = log2(blocksize) | log2(blocks per second-level scale) << 8 | (codebook != nullptr) << 16.
+template <int DT, int CLS>
+__global__ __launch_bounds__(kWave) void dequant_kernel(const uint8_t* __restrict__ packed,
+                                                        const float* __restrict__ absmax,
+                                                        uint16_t* __restrict__ out, int tiles, int shifts, int64_t n,
+                                                        const float* __restrict__ codebook) {
+    __shared__ uint32_t stage[kTileBytes / 4];
+    __shared__ float lut[16];
+    const ScaleArgs sa = {absmax, nullptr, nullptr, nullptr, nullptr, 8, (shifts >> 16) ? codebook : nullptr};
+    dequant_group<DT, false, CLS>(packed, sa, shifts & 0xff, n, tiles, out, blockIdx.x, stage, lut);
+}
+
+template <int DT, int CLS>
+__global__ __launch_bounds__(kWave) void dequant_dq_kernel(const uint8_t* __restrict__ packed,
+                                                           const uint8_t* __restrict__ q8,
+                                                           const float* __restrict__ scale2,
+                                                           const float* __restrict__ code2,
+                                                           const float* __restrict__ offset,
+                                                           uint16_t* __restrict__ out, int tiles, int shifts,
+                                                           int64_t n, const float* __restrict__ codebook) {
+    __shared__ uint32_t stage[kTileBytes / 4];
+    __shared__ float lut[16];
+    const ScaleArgs sa = {nullptr, q8, scale2, offset, code2, (shifts >> 8) & 0xff, (shifts >> 16) ? codebook : nullptr};
+    dequant_group<DT, true, CLS>(packed, sa, shifts & 0xff, n, tiles, out, blockIdx.x, stage, lut);
 }
 
 // Several tensors in one launch: workgroup g belongs to the tensor i with first_group[i] <= g <
@@ -172,7 +240,8 @@ struct BatchArgs {
     int count;
 };
 
-template <int DT, bool DQ>
+// The memory policy goes by the output of the whole launch (the tensors of a call are written side by side).
+template <int DT, bool DQ, int CLS>
 __global__ __launch_bounds__(kWave) void dequant_batch_kernel(BatchArgs ba, int log2_bs) {
     const int64_t g = blockIdx.x;
     int i = 0;
@@ -193,7 +262,9 @@ __global__ __launch_bounds__(kWave) void dequant_batch_kernel(BatchArgs ba, int 
             out = ba.out[k];
             n = ba.n[k]; tiles = ba.tiles[k]; first = ba.first_group[k];
         }
-    dequant_group<DT, DQ>(packed, sa, log2_bs, n, tiles, out, g - first);
+    __shared__ uint32_t stage[kTileBytes / 4];
+    __shared__ float lut[16];
+    dequant_group<DT, DQ, CLS>(packed, sa, log2_bs, n, tiles, out, g - first, stage, lut);
 }
 
 template <bool DQ>
@@ -222,10 +293,28 @@ static int launch(const uint8_t* packed, const ScaleArgs& sa, int blocksize, int
     hipStream_t s = (hipStream_t)stream;
     uint16_t* o = (uint16_t*)out;
     dim3 grid((unsigned)groups), block(kWave);
-    if (out_dtype == NF4_FP16)
-        hipLaunchKernelGGL((dequant_kernel<NF4_FP16, DQ>), grid, block, 0, s, packed, sa, log2_bs, n, tiles, o);
-    else
-        hipLaunchKernelGGL((dequant_kernel<NF4_BF16, DQ>), grid, block, 0, s, packed, sa, log2_bs, n, tiles, o);
+    const int shifts = log2_bs | (sa.log2_group << 8) | (sa.codebook ? 1 << 16 : 0);
+    const int t32 = (int)tiles;                                  // tiles <= groups < 2^31
+#define NF4_LAUNCH_DEQUANT(DT, CLS)                                                                              \
+    do {                                                                                                        \
+        if constexpr (DQ)                                                                                       \
+            hipLaunchKernelGGL((dequant_dq_kernel<DT, CLS>), grid, block, 0, s, packed, sa.q8, sa.scale2,       \
+                               sa.code2, sa.offset, o, t32, shifts, n, sa.codebook);                            \
+        else                                                                                                    \
+            hipLaunchKernelGGL((dequant_kernel<DT, CLS>), grid, block, 0, s, packed, sa.absmax, o, t32, shifts, \
+                               n, sa.codebook);                                                                 \
+    } while (0)
+    const OutClass cls = out_class(n);
+    if (out_dtype == NF4_FP16) {
+        if (cls == kOutSmall) NF4_LAUNCH_DEQUANT(NF4_FP16, kOutSmall);
+        else if (cls == kOutCached) NF4_LAUNCH_DEQUANT(NF4_FP16, kOutCached);
+        else NF4_LAUNCH_DEQUANT(NF4_FP16, kOutStream);
+    } else {
+        if (cls == kOutSmall) NF4_LAUNCH_DEQUANT(NF4_BF16, kOutSmall);
+        else if (cls == kOutCached) NF4_LAUNCH_DEQUANT(NF4_BF16, kOutCached);
+        else NF4_LAUNCH_DEQUANT(NF4_BF16, kOutStream);
+    }
+#undef NF4_LAUNCH_DEQUANT
     return record_hip(hipGetLastError());
 }
 
@@ -301,12 +390,22 @@ extern "C" int nf4_dequantize_batch(const nf4_tensor* tensors, int count, int bl
     if (groups > 0x7fffffffLL) return NF4_ERR_SIZE;
     hipStream_t s = (hipStream_t)stream;
     const dim3 grid((unsigned)groups), block(kWave);
-    if (out_dtype == NF4_FP16) {
-        if (dq) hipLaunchKernelGGL((dequant_batch_kernel<NF4_FP16, true>), grid, block, 0, s, ba, log2_bs);
-        else hipLaunchKernelGGL((dequant_batch_kernel<NF4_FP16, false>), grid, block, 0, s, ba, log2_bs);
-    } else {
-        if (dq) hipLaunchKernelGGL((dequant_batch_kernel<NF4_BF16, true>), grid, block, 0, s, ba, log2_bs);
-        else hipLaunchKernelGGL((dequant_batch_kernel<NF4_BF16, false>), grid, block, 0, s, ba, log2_bs);
-    }
+    int64_t total = 0;
+    for (int k = 0; k < ba.count; ++k) total += ba.n[k];
+#define NF4_LAUNCH_BATCH(CLS)                                                                                     \
+    do {                                                                                                         \
+        if (out_dtype == NF4_FP16) {                                                                             \
+            if (dq) hipLaunchKernelGGL((dequant_batch_kernel<NF4_FP16, true, CLS>), grid, block, 0, s, ba, log2_bs);  \
+            else hipLaunchKernelGGL((dequant_batch_kernel<NF4_FP16, false, CLS>), grid, block, 0, s, ba, log2_bs);    \
+        } else {                                                                                                 \
+            if (dq) hipLaunchKernelGGL((dequant_batch_kernel<NF4_BF16, true, CLS>), grid, block, 0, s, ba, log2_bs);  \
+            else hipLaunchKernelGGL((dequant_batch_kernel<NF4_BF16, false, CLS>), grid, block, 0, s, ba, log2_bs);    \
+        }                                                                                                        \
+    } while (0)
+    const OutClass cls = out_class(total);
+    if (cls == kOutSmall) NF4_LAUNCH_BATCH(kOutSmall);
+    else if (cls == kOutCached) NF4_LAUNCH_BATCH(kOutCached);
+    else NF4_LAUNCH_BATCH(kOutStream);
+#undef NF4_LAUNCH_BATCH
     return record_hip(hipGetLastError());
 }
