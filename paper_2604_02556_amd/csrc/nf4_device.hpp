@@ -118,11 +118,14 @@ constexpr int kPairReplicas = 32;
 constexpr int kPairTableBytes = 256 * kPairReplicas * 8;
 __device__ __forceinline__ uint32_t pair_lane_offset(int lane) { return (uint32_t)(lane & (kPairReplicas - 1)) * 8u; }
 
-// Fill the table from the 16 levels in `lut` (LDS, already visible to the caller's threads).
+// Fill the table from the 16 levels in `lut` (LDS, already visible to the caller's threads), two replicas of a
+// byte's pair per 128-bit write.
 __device__ __forceinline__ void fill_pair_table(float2_t* table, const float* lut, int tid, int threads) {
-    for (int i = tid; i < 256 * kPairReplicas; i += threads) {
-        const int byte = i / kPairReplicas;
-        table[i] = (float2_t){lut[byte >> 4], lut[byte & 15]};
+    typedef float float4_t __attribute__((ext_vector_type(4)));
+    for (int i = tid; i < 256 * kPairReplicas / 2; i += threads) {
+        const int byte = i / (kPairReplicas / 2);
+        const float e = lut[byte >> 4], o = lut[byte & 15];
+        ((float4_t*)table)[i] = (float4_t){e, o, e, o};
     }
 }
 
@@ -161,6 +164,23 @@ __device__ __forceinline__ void lds_wait() {
     __builtin_amdgcn_sched_barrier(0);
     __builtin_amdgcn_s_waitcnt(0xC07F | (LEFT << 8));              // lgkmcnt(LEFT); vmcnt, expcnt untouched
     __builtin_amdgcn_sched_barrier(0);
+}
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_add(float v) {
+    const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xF, false);
+    return v + __builtin_bit_cast(float, moved);
+}
+
+// Sum over the 64 lanes; the total lands in lane 63.
+__device__ __forceinline__ float wave_sum_to_lane63(float v) {
+    v = dpp_add<0xB1, 0xF>(v);    // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E, 0xF>(v);    // quad_perm [2,3,0,1]
+    v = dpp_add<0x114, 0xF>(v);   // row_shr:4
+    v = dpp_add<0x118, 0xF>(v);   // row_shr:8   -> lane 15 of each row holds the row sum
+    v = dpp_add<0x142, 0xA>(v);   // row_bcast:15 into rows 1 and 3
+    v = dpp_add<0x143, 0xC>(v);   // row_bcast:31 into rows 2 and 3
+    return v;
 }
 
 }  // namespace nf4

@@ -41,23 +41,6 @@ namespace nf4 {
 
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ float dpp_add(float v) {
-    const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xF, false);
-    return v + __builtin_bit_cast(float, moved);
-}
-
-// Sum over the 64 lanes; the total lands in lane 63.
-__device__ __forceinline__ float wave_sum_to_lane63(float v) {
-    v = dpp_add<0xB1, 0xF>(v);    // quad_perm [1,0,3,2]
-    v = dpp_add<0x4E, 0xF>(v);    // quad_perm [2,3,0,1]
-    v = dpp_add<0x114, 0xF>(v);   // row_shr:4
-    v = dpp_add<0x118, 0xF>(v);   // row_shr:8   -> lane 15 of each row holds the row sum
-    v = dpp_add<0x142, 0xA>(v);   // row_bcast:15 into rows 1 and 3
-    v = dpp_add<0x143, 0xC>(v);   // row_bcast:31 into rows 2 and 3
-    return v;
-}
-
 // One step's worth of operands for one lane.
 template <int B, int CH, int R>
 struct StepRegs {
@@ -497,6 +480,7 @@ static void launch_gemv(const uint8_t* packed, const uint8_t* q8, const float* s
 static int gemv_tokens(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
                        const float* code2, int log2_bs, int64_t N, int64_t K, const _Float16* x, int B,
                        _Float16* y, hipStream_t s) {
+    if (gemv_slice_eligible(N, K, B)) return launch_gemv_slice(packed, q8, scale2, offset, code2, log2_bs, N, K, x, B, y, s);
 #define NF4_GEMV_CASE(b, ch, r) \
     case b: launch_gemv<b, ch, r>(packed, q8, scale2, offset, code2, log2_bs, N, K, x, y, s); break;
     switch (B) {

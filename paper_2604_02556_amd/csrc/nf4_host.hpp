@@ -56,6 +56,12 @@ int launch_gemm_splitk(const uint8_t* packed, const uint8_t* q8, const float* sc
                        const float* code2, int log2_bs, int64_t N, int64_t K, const _Float16* x, int B,
                        _Float16* y, float* partial, bool gemv_weights, hipStream_t s);
 
+// One and two tokens by column slices (nf4_gemv_slice.hip): which shapes it takes, and the launch.
+bool gemv_slice_eligible(int64_t N, int64_t K, int B);
+int launch_gemv_slice(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
+                      const float* code2, int log2_bs, int64_t N, int64_t K, const _Float16* x, int B, _Float16* y,
+                      hipStream_t s);
+
 // nf4_dequant_gemv_ws after its argument checks: FMA kernels for one and two tokens, split-K on the matrix cores
 // with `partial` (plan_split(N, K, B).splits * B * N floats, written before they are read) above that.
 int launch_gemv_ws(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
