@@ -33,7 +33,6 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
-FP32_FMA_PEAK_TFLOPS = 157.3                        # FP32 vector peak: 256 CUs x 4 SIMDs x 32 lanes x 2 flop x 2.4 GHz
 BYTES_PER_ELEM = 0.5 + 4.0 / 64.0 + 2.0            # codes + fp32 absmax read, 16-bit value written
 BYTES_PER_ELEM_DQ = 0.5 + 1.0 / 64.0 + 4.0 / 16384.0 + 2.0
 GEMV_BYTES_PER_ELEM = 0.5 + 1.0 / 64.0 + 4.0 / 16384.0
@@ -50,6 +49,7 @@ def parse():
     ap.add_argument("--no-extra", action="store_true")
     ap.add_argument("--extra-legs", default="dq,gemv,quantize,layer,formats",
                     help="comma list of the extra legs to run: dq, gemv, quantize, layer")
+    ap.add_argument("--kernel-source-hash", action="store_true", help="print the hash profiles/dequant_fp16_70b_traffic.json is keyed to and exit")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="finish with one plain 256 MiB -> 256 MiB device copy (calibrates rocprofv3 byte counters)")
     return ap.parse_args()
@@ -57,6 +57,9 @@ def parse():
 
 def main():
     args = parse()
+    if args.kernel_source_hash:
+        print(kernel_source_hash())
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
               file=sys.stderr)
@@ -139,10 +142,18 @@ def main():
         "algorithmic_bytes_per_launch": round(bytes_per_launch, 1),
         "launches": launches,
     }
+    # HBM bytes per launch from the rocprofv3 counter runs recorded in profiles/ (counters cannot be read inside
+    # this run).  The record names the kernel source it was measured on; if the source has changed since, the
+    # figure is stale and is left out rather than reported.
     traffic_file = os.path.join(ROOT, "profiles", "dequant_fp16_70b_traffic.json")
     if os.path.exists(traffic_file):
         with open(traffic_file) as f:
-            roofline["traffic"] = json.load(f).get("hbm_bytes_per_launch")
+            rec = json.load(f)
+        if rec.get("kernel_source_sha256") == kernel_source_hash():
+            roofline["traffic"] = rec.get("hbm_bytes_per_launch")
+            roofline["traffic_source"] = "profiles/dequant_fp16_70b_traffic.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE)"
+        else:
+            roofline["traffic_source"] = "none: profiles/dequant_fp16_70b_traffic.json was measured on another version of the kernel"
 
     result = {
         "metric": METRIC, "value": round(value, 1), "unit": "GB/s",
@@ -184,6 +195,16 @@ def main():
         sample_layers = min(2, layers)                 # about 15 s of CPU work (1 s of wall time on 16 threads)
         result["cpu_baseline"] = cpu_baseline(tensors[:sample_layers * len(names)], sample_layers)
     print(json.dumps(result))
+
+
+def kernel_source_hash():
+    """sha256 over the sources of the dequantisation kernel (what profiles/dequant_fp16_70b_traffic.json is keyed to)."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in ("nf4_dequant.hip", "nf4_device.hpp"):
+        with open(os.path.join(ROOT, "paper_2604_02556_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
 
 
 def time_on_stream(torch, stream, fn, iters, warmup=2):
@@ -324,6 +345,26 @@ def leg_formats(torch, nf4, synth, stream, gen, src):
 GEMM_BATCHES = (1, 4, 16, 32, 64)
 
 
+def gemv_entry(n, B, us, kernel):
+    """Every token count up to 16 is priced against HBM: the codes and scale codes of W are read once (121.2 MB for
+    the 70B MLP shapes, 15.1 us at 8 TB/s) whatever B is, and from three tokens on the multiply-adds run on the
+    matrix cores, far from their peak."""
+    gbps = n * GEMV_BYTES_PER_ELEM / (us * 1e-6) / 1e9
+    return {"us": round(us, 2), "bound": "hbm", "GB/s": round(gbps, 1), "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
+            "TFLOP/s": round(2.0 * B * n / (us * 1e-6) / 1e12, 2), "kernel": kernel}
+
+
+def gemv_kernel_name(N, K, B, workspace):
+    """Which kernel the entry points choose (nf4_gemv.hip: mfma_min_tokens, kSplitMinTokens; nf4_gemv_slice.hip)."""
+    if B == 1 and 4096 <= K <= 32768:
+        return "gemv_slice_kernel (FP32 FMAs, column slices)"
+    if workspace and B >= 3:
+        return "gemm_splitk_kernel<SPLIT> + gemm_reduce_kernel (matrix cores, levels as two FP16 terms)"
+    if B >= (3 if N < 16384 else 5):
+        return "gemm_kernel<SPLIT> (matrix cores, levels as two FP16 terms)"
+    return "gemv_pair_kernel (FP32 FMAs)" if K >= 16384 else "gemv_kernel (FP32 FMAs)"
+
+
 def leg_gemv(torch, nf4, synth, stream, gen, src):
     """y = x W^T on the 70B MLP shapes, double-quantised W, batch 1/4/16; 8 distinct W copies (0.97 GB) are
     cycled so that the 112 MiB of codes come from HBM rather than the 256 MB last-level cache (with 4 copies
@@ -353,17 +394,7 @@ def leg_gemv(torch, nf4, synth, stream, gen, src):
                     nf4.nf4_dequant_gemv(b["packed"], b["absmax_q8"], b["scale2"], b["offset"], b["code2"], 64,
                                          N, K, x, B, y, stream=stream)
             us = time_on_stream(torch, stream, run, 5) / len(copies)
-            gbps = n * GEMV_BYTES_PER_ELEM / (us * 1e-6) / 1e9
-            tflops = 2.0 * B * n / (us * 1e-6) / 1e12
-            entry = {"us": round(us, 2), "GB/s": round(gbps, 1), "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
-                     "TFLOP/s": round(tflops, 2), "bound": "alu"}
-            if B < (3 if N < 16384 else 5):     # vector-ALU FMAs; for more tokens the entry point uses the matrix cores
-                entry["frac_of_fp32_fma_peak"] = round(tflops / FP32_FMA_PEAK_TFLOPS, 4)
-            else:
-                entry["kernel"] = ("matrix cores, levels as two FP16 terms, FP32 block scales; bound by LDS lookups "
-                                   "and, at 16 tokens, by every workgroup re-reading the activations from L2")
-                entry["bound"] = "lds/l2"
-            res[f"N{N}_K{K}_B{B}"] = entry
+            res[f"N{N}_K{K}_B{B}"] = gemv_entry(n, B, us, gemv_kernel_name(N, K, B, False))
             if B >= 3:      # with a caller workspace K is split across workgroups (nf4_dequant_gemv_ws)
                 ws = torch.empty(nf4.nf4_dequant_gemv_workspace_bytes(N, K, B), dtype=torch.uint8, device=dev)
 
@@ -372,11 +403,8 @@ def leg_gemv(torch, nf4, synth, stream, gen, src):
                         nf4.nf4_dequant_gemv_ws(b["packed"], b["absmax_q8"], b["scale2"], b["offset"], b["code2"], 64,
                                                 N, K, x, B, y, ws, stream=stream)
                 us = time_on_stream(torch, stream, run_ws, 5) / len(copies)
-                gbps = n * GEMV_BYTES_PER_ELEM / (us * 1e-6) / 1e9
-                res[f"ws_N{N}_K{K}_B{B}"] = {"us": round(us, 2), "GB/s": round(gbps, 1),
-                                             "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
-                                             "TFLOP/s": round(2.0 * B * n / (us * 1e-6) / 1e12, 2),
-                                             "workspace_bytes": int(ws.numel())}
+                res[f"ws_N{N}_K{K}_B{B}"] = dict(gemv_entry(n, B, us, gemv_kernel_name(N, K, B, True)),
+                                                 workspace_bytes=int(ws.numel()))
         # the matrix-core variant (weights rounded to FP16 in registers), the paper's batch range
         for B in GEMM_BATCHES:
             gen.manual_seed(6100 + B)

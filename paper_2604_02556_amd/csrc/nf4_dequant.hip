@@ -136,7 +136,6 @@ __device__ __forceinline__ void dequant_group(const uint8_t* __restrict__ packed
         const uint8_t* tile_codes = packed + t * kTileBytes;
         uint32_t code_off = (uint32_t)lane * 16u;
         u32x4 codes;
-        if constexpr (CLS == kOutSmall) codes = *(const u32x4*)(tile_codes + code_off);
         // Scales.  Lane l's k-th store covers elements e0 + 512 k + 8 l .. + 7,
         // all inside one quantisation block (blocksize >= 64).
         float s[4];
@@ -146,11 +145,28 @@ __device__ __forceinline__ void dequant_group(const uint8_t* __restrict__ packed
             const int per_tile = log2_bs >= 11 ? 1 : (kTileElems >> log2_bs);
             const int64_t b0 = e0 >> log2_bs;
             float mine = 0.0f;
-            if (lane < per_tile) mine = DQ ? dq_scale(sa, offset, b0 + lane) : sa.absmax[b0 + lane];
-            // the largest tensors: the address of the codes is made to depend on the scale, so that the wave
-            // requests its codes only when its scales are there
-            if constexpr (CLS == kOutStream) asm volatile("" : "+v"(code_off) : "v"(mine));
-            if constexpr (CLS != kOutSmall) codes = *(const u32x4*)(tile_codes + code_off);
+            if constexpr (DQ) {
+                // Two round trips to memory, not three: the 8-bit code and the second-level scale are requested
+                // first, the codes right behind them (vector loads complete in order, so the wave can wait for the
+                // first two alone), and the dependent read of the code2 map goes out while the codes are in flight.
+                // For the largest tensors the codes wait for the first round trip, as in the FP32-scale form.
+                // (lanes past the tile's blocks repeat its first block: no predicated loads, whose results the
+                // compiler would have to wait for at the end of the predicated region)
+                const int64_t blk = b0 + (lane < per_tile ? lane : 0);
+                const uint32_t q = sa.q8[blk];
+                const float s2 = sa.scale2[blk >> sa.log2_group];
+                if constexpr (CLS == kOutStream) asm volatile("" : "+v"(code_off) : "v"(q), "v"(s2));
+                codes = *(const u32x4*)(tile_codes + code_off);
+                const float prod = sa.code2[q] * s2;               // a rounded product, then a rounded sum (never an FMA)
+                mine = prod + offset;
+            } else {
+                if constexpr (CLS == kOutSmall) codes = *(const u32x4*)(tile_codes + code_off);
+                if (lane < per_tile) mine = sa.absmax[b0 + lane];
+                // the largest tensors: the address of the codes is made to depend on the scale, so that the wave
+                // requests its codes only when its scales are there
+                if constexpr (CLS == kOutStream) asm volatile("" : "+v"(code_off) : "v"(mine));
+                if constexpr (CLS != kOutSmall) codes = *(const u32x4*)(tile_codes + code_off);
+            }
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 const int src = log2_bs >= 11 ? 0 : ((512 * k + 8 * lane) >> log2_bs);
