@@ -5,7 +5,7 @@ the benchmark's CPU-baseline leg may import this package; the GPU library and
 its Python binding never do, and this package imports nothing of theirs.
 
 Every function cites the passage of the paper it follows in nf4_oracle.c.
-Parity unpinned: dq_encode (no external reference for the second-level
+Parity unpinned: dq_encode and dq_encode_group (no external reference for the second-level
 encoder; its decoder and invariants are pinned by tests).
 """
 import ctypes
@@ -49,6 +49,8 @@ def lib():
         L.nf4o_dequantize_dq_codebook.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, i64, vp, i32]
         L.nf4o_quantize_codebook.argtypes = [vp, i64, i32, vp, vp, vp]
         L.nf4o_dq_encode_group.argtypes = [vp, i64, i32, vp, vp, vp, vp]
+        L.nf4o_dequant_gemv_rows_codebook.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, i64, vp, i32, i64, i64, i32, vp, vp]
+        L.nf4o_dequant_gemv_rows_codebook.restype = None
         for name in ("nf4o_dequantize_codebook", "nf4o_dequantize_dq_codebook", "nf4o_quantize_codebook",
                      "nf4o_dq_encode_group"):
             getattr(L, name).restype = None
@@ -260,3 +262,27 @@ def dequantize_dq_codebook(packed, q8, scale2, offset, code2, group, codebook, n
     lib().nf4o_dequantize_dq_codebook(_p(packed), _p(q8), _p(scale2), _p(offset), _p(code2), group, _p(codebook),
                                       blocksize, n, _p(out), out_dtype)
     return out
+
+
+def dequant_gemv_rows_codebook(packed, q8, scale2, offset, code2, group, codebook, N, K, x_bits, r_first, r_count,
+                               blocksize=64, round_weights_to_fp16=False):
+    """dequant_gemv_rows (or, with round_weights_to_fp16, dequant_gemm_rows) for any 16 levels and any number of
+    blocks per second-level scale: (y_bits uint16[B][r_count], y float64[B][r_count])."""
+    x_bits = _chk(x_bits, np.uint16)
+    B = x_bits.size // K
+    n = N * K
+    nb = nblocks(n, blocksize)
+    packed = _chk(packed, np.uint8, (n + 1) // 2, "packed")
+    q8 = _chk(q8, np.uint8, nb, "absmax_q8")
+    scale2 = _chk(scale2, np.float32, (nb + group - 1) // group, "scale2")
+    offset = _chk(offset, np.float32, 1, "offset")
+    code2 = _chk(code2, np.float32, 256, "code2")
+    codebook = _chk(codebook, np.float32, 16, "codebook")
+    if r_first < 0 or r_first + r_count > N:
+        raise ValueError("row range outside the matrix")
+    y = np.empty((B, r_count), dtype=np.uint16)
+    y64 = np.empty((B, r_count), dtype=np.float64)
+    lib().nf4o_dequant_gemv_rows_codebook(_p(packed), _p(q8), _p(scale2), _p(offset), _p(code2), group, _p(codebook),
+                                          blocksize, K, _p(x_bits), B, r_first, r_count,
+                                          1 if round_weights_to_fp16 else 0, _p(y), _p(y64))
+    return y, y64

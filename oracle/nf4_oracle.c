@@ -414,3 +414,32 @@ void nf4o_dq_encode_group(const float *absmax, int64_t nb, int group, uint8_t *a
         }
     }
 }
+
+/* The fused products for any table and group size: the same sums as
+ * nf4o_dequant_gemv_rows (weight = the FP32 product table[code] * scale, never
+ * rounded to 16 bits) and nf4o_dequant_gemm_rows (weight rounded to FP16 first,
+ * Sec. III-A), with the scale of nf4o_dequantize_dq_codebook.  Accumulated in
+ * double in index order.  Rows [r_first, r_first + r_count). */
+void nf4o_dequant_gemv_rows_codebook(const uint8_t *packed, const uint8_t *absmax_q8,
+                                     const float *scale2, const float *offset, const float *code2,
+                                     int group, const float *table, int blocksize, int64_t K,
+                                     const uint16_t *x, int B, int64_t r_first, int64_t r_count,
+                                     int round_weights_to_fp16, uint16_t *y, double *y_f64) {
+    for (int b = 0; b < B; ++b) {
+        for (int64_t r = r_first; r < r_first + r_count; ++r) {
+            double acc = 0.0;
+            for (int64_t k = 0; k < K; ++k) {
+                int64_t i = r * K + k;
+                int64_t blk = i / blocksize;
+                float prod = code2[absmax_q8[blk]] * scale2[blk / group];
+                float scale = prod + offset[0];
+                float w = table[code_of(packed, i)] * scale;
+                double wd = round_weights_to_fp16 ? f16_bits_to_double(nf4o_f32_to_f16(w)) : (double)w;
+                acc += f16_bits_to_double(x[(int64_t)b * K + k]) * wd;
+            }
+            int64_t o = (int64_t)b * r_count + (r - r_first);
+            if (y_f64) y_f64[o] = acc;
+            if (y) y[o] = nf4o_f32_to_f16((float)acc);
+        }
+    }
+}

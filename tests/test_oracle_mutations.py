@@ -43,6 +43,12 @@ MUTATIONS = [
      "float d = fabsf(xn - table[k]);\n        if (d <= best_d) { best_d = d; best = k; }"),
     ("codebook quantiser zero code fixed at 7", "unsigned zero_code = nearest_code(table, 0.0f);", "unsigned zero_code = 7;"),
     ("group encoder strides by 256", "int64_t lo = g * group;", "int64_t lo = g * 256;"),
+    ("codebook gemv ignores its table", "float w = table[code_of(packed, i)] * scale;", "float w = NF4_LEVEL[code_of(packed, i)] * scale;"),
+    ("codebook gemv uses groups of 256", "float prod = code2[absmax_q8[blk]] * scale2[blk / group];",
+     "float prod = code2[absmax_q8[blk]] * scale2[blk / 256];"),
+    ("codebook gemv always rounds its weights", "double wd = round_weights_to_fp16 ? f16_bits_to_double(nf4o_f32_to_f16(w)) : (double)w;",
+     "double wd = f16_bits_to_double(nf4o_f32_to_f16(w));"),
+    ("codebook gemv indexes blocks by the column alone", "int64_t blk = i / blocksize;", "int64_t blk = k / blocksize;"),
 ]
 
 

@@ -512,3 +512,48 @@ def test_dequantize_dq_codebook_equals_decode_then_dequantize():
             want = oracle.dequantize_codebook(p, dec, t, n, blocksize=128, out_dtype=dt)
             got = oracle.dequantize_dq_codebook(p, q8, s2, off, c2, group, t, n, blocksize=128, out_dtype=dt)
             assert np.array_equal(want, got)
+
+
+def test_codebook_gemv_and_gemm_are_float64_matmuls_of_the_codebook_weights():
+    """The fused products for any table and group size: with the NF4 table and groups of 256 they are the NF4
+    functions bit for bit; with another table, block size and group size they equal a float64 matmul of the weights
+    that dequantize_dq_codebook yields (FP32 for the GEMV, rounded to FP16 for the GEMM), a unit vector picks
+    a column exactly, and a row range is a slice of the whole."""
+    N, K, B = 24, 256, 3
+    p, q8, s2, off, c2, x = _small_gemv_case(N, K, B, seed=61)
+    xb = x.view(np.uint16)
+    for rnd, plain in ((False, oracle.dequant_gemv_rows), (True, oracle.dequant_gemm_rows)):
+        yb, y64 = plain(p, q8, s2, off, c2, N, K, xb, 0, N)
+        cb, c64 = oracle.dequant_gemv_rows_codebook(p, q8, s2, off, c2, 256, oracle.table(), N, K, xb, 0, N,
+                                                    round_weights_to_fp16=rnd)
+        assert np.array_equal(yb, cb) and np.array_equal(y64, c64)
+    t = e2m1_codebook()
+    rng = np.random.Generator(np.random.PCG64(62))
+    N, K, bs, group = 20, 512, 128, 4
+    w = (rng.standard_normal(N * K) * 0.02).astype(np.float32)
+    p, a = oracle.quantize_codebook(w, t, blocksize=bs)
+    q8, s2, off, c2 = oracle.dq_encode_group(a, group)
+    x = synth.activations_fp16(B, K, 63)
+    xb = x.view(np.uint16)
+    w32 = oracle.dequantize_dq_codebook(p, q8, s2, off, c2, group, t, N * K, blocksize=bs, out_dtype=oracle.FP32)
+    w16 = f16(oracle.dequantize_dq_codebook(p, q8, s2, off, c2, group, t, N * K, blocksize=bs, out_dtype=oracle.FP16))
+    for rnd, wref in ((False, w32), (True, w16)):
+        wref = wref.reshape(N, K).astype(np.float64)
+        yb, y64 = oracle.dequant_gemv_rows_codebook(p, q8, s2, off, c2, group, t, N, K, xb, 0, N, blocksize=bs,
+                                                    round_weights_to_fp16=rnd)
+        want = x.astype(np.float64) @ wref.T
+        assert np.allclose(y64, want, rtol=1e-12, atol=1e-12)
+        assert np.array_equal(yb, want.astype(np.float32).astype(np.float16).view(np.uint16))
+        e = np.zeros((1, K), np.float16)
+        e[0, 300] = 1
+        _, col = oracle.dequant_gemv_rows_codebook(p, q8, s2, off, c2, group, t, N, K, e.view(np.uint16), 0, N,
+                                                   blocksize=bs, round_weights_to_fp16=rnd)
+        assert np.array_equal(col[0], wref[:, 300])
+        _, part = oracle.dequant_gemv_rows_codebook(p, q8, s2, off, c2, group, t, N, K, xb, 7, 5, blocksize=bs,
+                                                    round_weights_to_fp16=rnd)
+        assert np.array_equal(part, y64[:, 7:12])
+    # the rounding flag matters: the two products differ, slightly
+    _, a64 = oracle.dequant_gemv_rows_codebook(p, q8, s2, off, c2, group, t, N, K, xb, 0, N, blocksize=bs)
+    _, b64 = oracle.dequant_gemv_rows_codebook(p, q8, s2, off, c2, group, t, N, K, xb, 0, N, blocksize=bs,
+                                               round_weights_to_fp16=True)
+    assert not np.array_equal(a64, b64) and np.allclose(a64, b64, rtol=0, atol=2e-3 * np.abs(a64).max())
