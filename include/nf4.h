@@ -223,6 +223,31 @@ int nf4_dequantize_dq_codebook(const uint8_t* packed, const uint8_t* absmax_q8, 
                                int out_dtype, void* stream);
 
 /*
+ * The fused products with the data type as a parameter (Sec. V-A), for tensors
+ * made by nf4_quantize_ref_codebook / nf4_dq_encode with another table or group
+ * size: nf4_dequant_gemv / nf4_dequant_gemv_ws and nf4_dequant_gemm with
+ * `codebook` (16 FP32 levels, device, 4-byte aligned; NULL = the NF4 levels) and
+ * `dq_group` (blocks per second-level scale, a power of two in [1, 65536], else
+ * NF4_ERR_SHAPE) as in nf4_dequantize_dq_codebook.  Everything else -- the
+ * definition of y, layouts, limits, the kernels chosen -- is that of the calls
+ * without these two arguments, which are these calls with NULL and 256 and
+ * accept no other format.  workspace == NULL selects the form without a
+ * workspace (nf4_dequant_gemv; the single kernel of nf4_dequant_gemm), a
+ * workspace of nf4_dequant_gemv_workspace_bytes / nf4_dequant_gemm_workspace_bytes
+ * the form with one.
+ */
+int nf4_dequant_gemv_codebook(const uint8_t* packed, const uint8_t* absmax_q8, const float* scale2,
+                              const float* offset, const float* code2, int dq_group,
+                              const float* codebook, int blocksize, int64_t N, int64_t K,
+                              const void* x, int B, void* y, void* workspace, size_t workspace_bytes,
+                              void* stream);
+int nf4_dequant_gemm_codebook(const uint8_t* packed, const uint8_t* absmax_q8, const float* scale2,
+                              const float* offset, const float* code2, int dq_group,
+                              const float* codebook, int blocksize, int64_t N, int64_t K,
+                              const void* x, int B, void* y, void* workspace, size_t workspace_bytes,
+                              void* stream);
+
+/*
  * Reference-quality (untuned) quantiser, the forward direction of Sec. II-B:
  * per block absmax = max |src|, code = nearest level to src / absmax (FP32
  * distance, ties to the lower index, all-zero block -> absmax 0 and code 7,

@@ -58,6 +58,9 @@ def lib():
     L.nf4_dequant_gemv_static.argtypes = [vp, vp, vp, vp, vp, i32, i64, i64, vp, i32, vp, vp]
     L.nf4_dequant_gemv_static.restype = i32
     L.nf4_dequant_gemv_workspace_bytes.restype = c.c_size_t
+    for f in (L.nf4_dequant_gemv_codebook, L.nf4_dequant_gemm_codebook):
+        f.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, i64, i64, vp, i32, vp, vp, c.c_size_t, vp]
+        f.restype = i32
     L.nf4_quantize_ref.argtypes = [vp, i64, i32, vp, vp, vp, vp, vp, vp, vp]
     L.nf4_dequantize_codebook.argtypes = [vp, vp, vp, i32, i64, vp, i32, vp]
     L.nf4_dequantize_dq_codebook.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, i64, vp, i32, vp]
@@ -190,6 +193,26 @@ def nf4_dequant_gemm(packed, absmax_q8, scale2, offset, code2, blocksize, N, K, 
     _check(lib().nf4_dequant_gemm(_ptr(packed), _ptr(absmax_q8), _ptr(scale2), _ptr(offset), _ptr(code2),
                                   blocksize, N, K, _ptr(x), B, _ptr(y), _ptr(workspace), ws_bytes,
                                   _stream(stream)))
+    return y
+
+
+def nf4_dequant_gemv_codebook(packed, absmax_q8, scale2, offset, code2, dq_group, codebook, blocksize, N, K, x, B, y,
+                              workspace=None, stream=None):
+    """nf4_dequant_gemv (workspace None) or nf4_dequant_gemv_ws for any 16 levels and second-level group size."""
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().nf4_dequant_gemv_codebook(_ptr(packed), _ptr(absmax_q8), _ptr(scale2), _ptr(offset), _ptr(code2),
+                                           dq_group, _ptr(codebook), blocksize, N, K, _ptr(x), B, _ptr(y),
+                                           _ptr(workspace), ws_bytes, _stream(stream)))
+    return y
+
+
+def nf4_dequant_gemm_codebook(packed, absmax_q8, scale2, offset, code2, dq_group, codebook, blocksize, N, K, x, B, y,
+                              workspace=None, stream=None):
+    """nf4_dequant_gemm for any 16 levels and second-level group size."""
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().nf4_dequant_gemm_codebook(_ptr(packed), _ptr(absmax_q8), _ptr(scale2), _ptr(offset), _ptr(code2),
+                                           dq_group, _ptr(codebook), blocksize, N, K, _ptr(x), B, _ptr(y),
+                                           _ptr(workspace), ws_bytes, _stream(stream)))
     return y
 
 

@@ -60,7 +60,7 @@ __global__ __launch_bounds__(kMWaves * kWave) void gemm_kernel(const uint8_t* __
                                                                const float* __restrict__ scale2,
                                                                const float* __restrict__ offset_p,
                                                                const float* __restrict__ code2, int log2_bs,
-                                                               int64_t N, int64_t K,
+                                                               Fmt fmt, int64_t N, int64_t K,
                                                                const _Float16* __restrict__ x, int B,
                                                                _Float16* __restrict__ y) {
     constexpr int kMThreads = kMWaves * kWave;
@@ -77,7 +77,8 @@ __global__ __launch_bounds__(kMWaves * kWave) void gemm_kernel(const uint8_t* __
     float (*red)[kTiles * 4][kWave] = (float (*)[kTiles * 4][kWave])smem;
 
     const int tid = threadIdx.x;
-    if (tid < 16) lut[tid] = __uint_as_float(level_literal(tid));
+    const int lg = fmt.log2_group;
+    if (tid < 16) lut[tid] = fmt.codebook ? fmt.codebook[tid] : __uint_as_float(level_literal(tid));
     for (int i = tid; i < 256; i += kMThreads) code2_lds[i] = code2[i];
     __syncthreads();
     static_assert(!SPLIT || PAIR, "the split levels live in the pair table's space");
@@ -126,7 +127,7 @@ __global__ __launch_bounds__(kMWaves * kWave) void gemm_kernel(const uint8_t* __
             mine[r] = 0.0f;
             if (row_ok && kw + 64 * g < K) {
                 const int64_t blk = (e0 + 64 * g) >> log2_bs;
-                const float prod = code2_lds[q8[blk]] * scale2[blk >> 8];    // rounded product, then rounded sum
+                const float prod = code2_lds[q8[blk]] * scale2[blk >> lg];   // rounded product, then rounded sum
                 mine[r] = prod + offset;
             }
         }
@@ -251,20 +252,20 @@ __global__ __launch_bounds__(kMWaves * kWave) void gemm_kernel(const uint8_t* __
 
 template <int TG, int RG, int W, bool SPLIT = false, bool PAIR = false>
 static void launch_gemm(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
-                        const float* code2, int log2_bs, int64_t N, int64_t K, const _Float16* x, int B,
+                        const float* code2, int log2_bs, Fmt fmt, int64_t N, int64_t K, const _Float16* x, int B,
                         _Float16* y, hipStream_t s) {
     const unsigned groups = (unsigned)((N + 16 * RG - 1) / (16 * RG));
     hipLaunchKernelGGL((gemm_kernel<TG, RG, W, SPLIT, PAIR>), dim3(groups), dim3(W * kWave), 0, s, packed, q8, scale2, offset, code2,
-                       log2_bs, N, K, x, B, y);
+                       log2_bs, fmt, N, K, x, B, y);
 }
 
 // y = x W^T with W = level * scale on the matrix cores (levels as two FP16 terms, FP32 block scales), at most 16
 // tokens.  One shape for all matrices: two row groups per workgroup of 16 waves (four and one row groups, and 8
 // waves, all measured slower on 28672 x 8192: 77, 62-92 and more us against 54-56).
 int launch_gemv_mfma(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
-                     const float* code2, int log2_bs, int64_t N, int64_t K, const _Float16* x, int B, _Float16* y,
-                     hipStream_t s) {
-    launch_gemm<1, 2, 16, true, true>(packed, q8, scale2, offset, code2, log2_bs, N, K, x, B, y, s);
+                     const float* code2, int log2_bs, Fmt fmt, int64_t N, int64_t K, const _Float16* x, int B,
+                     _Float16* y, hipStream_t s) {
+    launch_gemm<1, 2, 16, true, true>(packed, q8, scale2, offset, code2, log2_bs, fmt, N, K, x, B, y, s);
     return record_hip(hipGetLastError());
 }
 
@@ -277,12 +278,12 @@ extern "C" size_t nf4_dequant_gemm_workspace_bytes(int64_t N, int64_t K, int B) 
     return p.splits > 1 ? (size_t)p.splits * (size_t)B * (size_t)N * sizeof(float) : 16;
 }
 
-extern "C" int nf4_dequant_gemm(const uint8_t* packed, const uint8_t* absmax_q8, const float* scale2,
-                                const float* offset, const float* code2, int blocksize, int64_t N,
-                                int64_t K, const void* x, int B, void* y, void* workspace,
-                                size_t workspace_bytes, void* stream) {
-    using namespace nf4;
+namespace nf4 {
+static int gemm_entry(const uint8_t* packed, const uint8_t* absmax_q8, const float* scale2, const float* offset,
+                      const float* code2, int blocksize, Fmt fmt, int64_t N, int64_t K, const void* x, int B, void* y,
+                      void* workspace, size_t workspace_bytes, void* stream) {
     if (N < 0 || K < 0) return NF4_ERR_SIZE;
+    if (fmt.log2_group < 0) return NF4_ERR_SHAPE;
     const int log2_bs = log2_blocksize(blocksize);
     if (log2_bs < 0) return NF4_ERR_BLOCKSIZE;
     if (B < 1 || B > 64) return NF4_ERR_SHAPE;
@@ -291,7 +292,7 @@ extern "C" int nf4_dequant_gemm(const uint8_t* packed, const uint8_t* absmax_q8,
     if (N == 0) return NF4_OK;
     if (!packed || !absmax_q8 || !scale2 || !offset || !code2 || !x || !y) return NF4_ERR_NULL;
     if (!aligned(packed, 16) || !aligned(x, 16) || !aligned(y, 2) || !aligned(scale2, 4) || !aligned(offset, 4) ||
-        !aligned(code2, 4))
+        !aligned(code2, 4) || !aligned(fmt.codebook, 4))
         return NF4_ERR_ALIGN;
     hipStream_t s = (hipStream_t)stream;
     const _Float16* xp = (const _Float16*)x;
@@ -299,14 +300,14 @@ extern "C" int nf4_dequant_gemm(const uint8_t* packed, const uint8_t* absmax_q8,
     if (workspace) {
         if (!aligned(workspace, 16)) return NF4_ERR_ALIGN;
         if (workspace_bytes < nf4_dequant_gemm_workspace_bytes(N, K, B)) return NF4_ERR_SIZE;
-        return launch_gemm_splitk(packed, absmax_q8, scale2, offset, code2, log2_bs, N, K, xp, B, yp,
+        return launch_gemm_splitk(packed, absmax_q8, scale2, offset, code2, log2_bs, fmt, N, K, xp, B, yp,
                                   (float*)workspace, false, s);
     }
     // (token groups, row groups per wave, waves per workgroup = split of K), picked by sweeping on MI355X:
     // sharing the activation registers between row groups halves the L2 traffic that bounds this kernel,
     // but matrices with few rows need the smaller tile to fill the machine.
     const bool tall = N >= 16384;
-#define NF4_GEMM_ARGS packed, absmax_q8, scale2, offset, code2, log2_bs, N, K, xp, B, yp, s
+#define NF4_GEMM_ARGS packed, absmax_q8, scale2, offset, code2, log2_bs, fmt, N, K, xp, B, yp, s
     switch ((B + 15) / 16) {
         case 1: if (tall) launch_gemm<1, 2, 8>(NF4_GEMM_ARGS); else launch_gemm<1, 2, 16>(NF4_GEMM_ARGS); break;
         // 17..32 tokens: the reduction buffer already takes the LDS that the pair table needs, so it is free
@@ -319,4 +320,23 @@ extern "C" int nf4_dequant_gemm(const uint8_t* packed, const uint8_t* absmax_q8,
     }
 #undef NF4_GEMM_ARGS
     return record_hip(hipGetLastError());
+}
+}  // namespace nf4
+
+extern "C" int nf4_dequant_gemm(const uint8_t* packed, const uint8_t* absmax_q8, const float* scale2,
+                                const float* offset, const float* code2, int blocksize, int64_t N,
+                                int64_t K, const void* x, int B, void* y, void* workspace,
+                                size_t workspace_bytes, void* stream) {
+    return nf4::gemm_entry(packed, absmax_q8, scale2, offset, code2, blocksize, nf4::kNf4Fmt, N, K, x, B, y, workspace,
+                           workspace_bytes, stream);
+}
+
+// the data type as a parameter (Sec. V-A): any 16 levels, any second-level group size
+extern "C" int nf4_dequant_gemm_codebook(const uint8_t* packed, const uint8_t* absmax_q8, const float* scale2,
+                                         const float* offset, const float* code2, int dq_group,
+                                         const float* codebook, int blocksize, int64_t N, int64_t K, const void* x,
+                                         int B, void* y, void* workspace, size_t workspace_bytes, void* stream) {
+    const nf4::Fmt fmt = {nf4::log2_dq_group(dq_group), codebook};
+    return nf4::gemm_entry(packed, absmax_q8, scale2, offset, code2, blocksize, fmt, N, K, x, B, y, workspace,
+                           workspace_bytes, stream);
 }

@@ -65,7 +65,7 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
                                                                 const float* __restrict__ scale2,
                                                                 const float* __restrict__ offset_p,
                                                                 const float* __restrict__ code2, int log2_bs,
-                                                                int64_t N, int64_t K,
+                                                                Fmt fmt, int64_t N, int64_t K,
                                                                 const _Float16* __restrict__ x, int B, int wps,
                                                                 float* __restrict__ partial,
                                                                 _Float16* __restrict__ y) {
@@ -95,7 +95,8 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
     float* lut = (float*)(smem + kOffLut);
 
     const int tid = threadIdx.x;
-    if (tid < 16) lut[tid] = __uint_as_float(level_literal(tid));
+    const int lg = fmt.log2_group;
+    if (tid < 16) lut[tid] = fmt.codebook ? fmt.codebook[tid] : __uint_as_float(level_literal(tid));
     for (int i = tid; i < 256; i += kThreads) code2_lds[i] = code2[i];
     __syncthreads();
     // visible after the barrier that follows the first tile
@@ -143,8 +144,8 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
             const int64_t ub = u >> log2_bs;
             const uint32_t ulow = (uint32_t)(u & ((int64_t(1) << log2_bs) - 1));
             const uint8_t* qbase = q8 + ub;
-            const float* sbase = scale2 + (ub >> 8);
-            const uint32_t ub_low = (uint32_t)(ub & 255);
+            const float* sbase = scale2 + (ub >> lg);
+            const uint32_t ub_low = (uint32_t)(ub & ((int64_t(1) << lg) - 1));
 #pragma unroll
             for (int r = 0; r < RG; ++r) {
                 const uint32_t v = (uint32_t)(16 * r + lrow) * (uint32_t)K;       // elements past u
@@ -155,7 +156,7 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
                 for (int m = 0; m < kH / 2; ++m) {
                     const uint32_t lb = (ulow + v + 64u * (lpc + 4 * m)) >> log2_bs;   // blocks past ub
                     cr.qb[r][m] = qbase[lb];
-                    cr.s2[r][m] = sbase[(ub_low + lb) >> 8];
+                    cr.s2[r][m] = sbase[(ub_low + lb) >> lg];
                 }
             }
             return;
@@ -178,7 +179,7 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
                 if (row_ok && kw + 64 * (lpc + 4 * m) < k_end) {
                     const int64_t blk = (e0 + 64 * (lpc + 4 * m)) >> log2_bs;
                     cr.qb[r][m] = q8[blk];
-                    cr.s2[r][m] = scale2[blk >> 8];
+                    cr.s2[r][m] = scale2[blk >> lg];
                 }
             }
         }
@@ -432,18 +433,18 @@ SplitPlan plan_split(int64_t N, int64_t K, int B) {
 
 template <int TG, int RG, int W, bool SPLIT = false>
 static void launch_splitk(const SplitPlan& p, const uint8_t* packed, const uint8_t* q8, const float* scale2,
-                          const float* offset, const float* code2, int log2_bs, int64_t N, int64_t K,
+                          const float* offset, const float* code2, int log2_bs, Fmt fmt, int64_t N, int64_t K,
                           const _Float16* x, int B, float* partial, _Float16* y, hipStream_t s) {
     hipLaunchKernelGGL((gemm_splitk_kernel<TG, RG, W, window_of(TG), SPLIT>), dim3((unsigned)p.row_blocks, (unsigned)p.splits),
-                       dim3(W * kWave), 0, s, packed, q8, scale2, offset, code2, log2_bs, N, K, x, B, p.wps,
+                       dim3(W * kWave), 0, s, packed, q8, scale2, offset, code2, log2_bs, fmt, N, K, x, B, p.wps,
                        p.splits > 1 ? partial : nullptr, y);
 }
 
 int launch_gemm_splitk(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
-                       const float* code2, int log2_bs, int64_t N, int64_t K, const _Float16* x, int B,
+                       const float* code2, int log2_bs, Fmt fmt, int64_t N, int64_t K, const _Float16* x, int B,
                        _Float16* y, float* partial, bool gemv_weights, hipStream_t s) {
     const SplitPlan p = plan_split(N, K, B);
-#define NF4_SK_ARGS p, packed, q8, scale2, offset, code2, log2_bs, N, K, x, B, partial, y, s
+#define NF4_SK_ARGS p, packed, q8, scale2, offset, code2, log2_bs, fmt, N, K, x, B, partial, y, s
     switch (p.tg) {
         case 1:
             if (gemv_weights) launch_splitk<1, 1, 16, true>(NF4_SK_ARGS);     // at most 16 tokens

@@ -56,8 +56,8 @@ template <int R>
 struct RowBases {
     const uint8_t* codes[R];   // packed + row_start / 2
     const uint8_t* q8[R];      // q8 + row_start / blocksize
-    uint32_t blk_lo[R];        // (row_start / blocksize) mod 256
-    const float* s2[R];        // scale2 + (row_start / blocksize) / 256
+    uint32_t blk_lo[R];        // (row_start / blocksize) mod group (blocks per second-level scale)
+    const float* s2[R];        // scale2 + (row_start / blocksize) / group
 };
 
 // Loads of one step.  `k0` (first element of the step) is wave-uniform, so every
@@ -65,7 +65,7 @@ struct RowBases {
 // FULL: every lane chunk is inside K and all R rows exist, so nothing is predicated.
 template <int B, int CH, int R, bool FULL>
 __device__ __forceinline__ void load_step(StepRegs<B, CH, R>& g, const RowBases<R>& rb,
-                                          const _Float16* __restrict__ x, int log2_bs, int64_t K, int rows,
+                                          const _Float16* __restrict__ x, int log2_bs, int lg, int64_t K, int rows,
                                           int64_t k0, int lane) {
     constexpr int E = 8 * CH;
     typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -92,8 +92,8 @@ __device__ __forceinline__ void load_step(StepRegs<B, CH, R>& g, const RowBases<
                 }
                 g.q8[r] = (rb.q8[r] + kb)[vb];
                 const int64_t gb = (int64_t)rb.blk_lo[r] + kb;     // block index relative to the row's group base
-                const uint32_t vg = ((uint32_t)(gb & 255) + vb) >> 8;
-                g.s2[r] = (rb.s2[r] + (gb >> 8))[vg];
+                const uint32_t vg = ((uint32_t)(gb & ((int64_t(1) << lg) - 1)) + vb) >> lg;
+                g.s2[r] = (rb.s2[r] + (gb >> lg))[vg];
             } else {                                               // rows past N: level 0, scale code 0
 #pragma unroll
                 for (int c = 0; c < CH; ++c) g.q[r][c] = 0x77777777u;
@@ -255,8 +255,8 @@ __global__ __launch_bounds__(kWave, 2) void gemv_kernel(const uint8_t* __restric
                                                      const uint8_t* __restrict__ q8,
                                                      const float* __restrict__ scale2,
                                                      const float* __restrict__ offset_p,
-                                                     const float* __restrict__ code2, int log2_bs, int64_t N,
-                                                     int64_t K, const _Float16* __restrict__ x,
+                                                     const float* __restrict__ code2, int log2_bs, Fmt fmt,
+                                                     int64_t N, int64_t K, const _Float16* __restrict__ x,
                                                      _Float16* __restrict__ y) {
     constexpr int E = 8 * CH;                 // elements per lane per step
     constexpr int kSlice = E * kWave;         // elements per wave per step
@@ -264,7 +264,8 @@ __global__ __launch_bounds__(kWave, 2) void gemv_kernel(const uint8_t* __restric
     __shared__ float code2_lds[256];
 
     const int lane = threadIdx.x;
-    if (lane < 16) lut[lane] = __uint_as_float(level_literal(lane));
+    const int lg = fmt.log2_group;
+    if (lane < 16) lut[lane] = fmt.codebook ? fmt.codebook[lane] : __uint_as_float(level_literal(lane));
 #pragma unroll
     for (int i = 0; i < 4; ++i) code2_lds[lane + 64 * i] = code2[lane + 64 * i];
     wave_lds_fence();
@@ -290,16 +291,16 @@ __global__ __launch_bounds__(kWave, 2) void gemv_kernel(const uint8_t* __restric
         const int64_t row_blk = row_start >> log2_bs;
         rb.codes[r] = packed + (row_start >> 1);
         rb.q8[r] = q8 + row_blk;
-        rb.blk_lo[r] = (uint32_t)(row_blk & 255);
-        rb.s2[r] = scale2 + (row_blk >> 8);
+        rb.blk_lo[r] = (uint32_t)(row_blk & ((int64_t(1) << lg) - 1));
+        rb.s2[r] = scale2 + (row_blk >> lg);
     }
     StepRegs<B, CH, R> ping, pong;
-    load_step<B, CH, R, FULL>(ping, rb, x, log2_bs, K, rows, 0, lane);
+    load_step<B, CH, R, FULL>(ping, rb, x, log2_bs, lg, K, rows, 0, lane);
     for (int64_t it = 0;;) {
-        if (it + 1 < steps) load_step<B, CH, R, FULL>(pong, rb, x, log2_bs, K, rows, (it + 1) * kSlice, lane);
+        if (it + 1 < steps) load_step<B, CH, R, FULL>(pong, rb, x, log2_bs, lg, K, rows, (it + 1) * kSlice, lane);
         compute_step<B, CH, R>(ping, lut, code2_lds, offset, acc);
         if (++it >= steps) break;
-        if (it + 1 < steps) load_step<B, CH, R, FULL>(ping, rb, x, log2_bs, K, rows, (it + 1) * kSlice, lane);
+        if (it + 1 < steps) load_step<B, CH, R, FULL>(ping, rb, x, log2_bs, lg, K, rows, (it + 1) * kSlice, lane);
         compute_step<B, CH, R>(pong, lut, code2_lds, offset, acc);
         if (++it >= steps) break;
     }
@@ -364,7 +365,7 @@ __global__ __launch_bounds__(kPairWaves * kWave) void gemv_pair_kernel(const uin
                                                                        const float* __restrict__ scale2,
                                                                        const float* __restrict__ offset_p,
                                                                        const float* __restrict__ code2, int log2_bs,
-                                                                       int64_t N, int64_t K,
+                                                                       Fmt fmt, int64_t N, int64_t K,
                                                                        const _Float16* __restrict__ x,
                                                                        _Float16* __restrict__ y) {
     constexpr int E = 8 * CH;
@@ -380,7 +381,8 @@ __global__ __launch_bounds__(kPairWaves * kWave) void gemv_pair_kernel(const uin
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    if (tid < 16) lut[tid] = __uint_as_float(level_literal(tid));
+    const int lg = fmt.log2_group;
+    if (tid < 16) lut[tid] = fmt.codebook ? fmt.codebook[tid] : __uint_as_float(level_literal(tid));
     for (int i = tid; i < 256; i += kThreads) code2_lds[i] = code2[i];
     __syncthreads();
     fill_pair_table((float2_t*)smem, lut, tid, kThreads);
@@ -406,8 +408,8 @@ __global__ __launch_bounds__(kPairWaves * kWave) void gemv_pair_kernel(const uin
         const int64_t row_blk = row_start >> log2_bs;
         rb.codes[r] = packed + (row_start >> 1);
         rb.q8[r] = q8 + row_blk;
-        rb.blk_lo[r] = (uint32_t)(row_blk & 255);
-        rb.s2[r] = scale2 + (row_blk >> 8);
+        rb.blk_lo[r] = (uint32_t)(row_blk & ((int64_t(1) << lg) - 1));
+        rb.s2[r] = scale2 + (row_blk >> lg);
     }
     StepRegs<B, CH, R> ping, pong;
     if constexpr (MERGED) {
@@ -423,12 +425,12 @@ __global__ __launch_bounds__(kPairWaves * kWave) void gemv_pair_kernel(const uin
             if (++it >= steps) break;
         }
     } else {
-        load_step<B, CH, R, FULL>(ping, rb, x, log2_bs, K, rows, 0, lane);
+        load_step<B, CH, R, FULL>(ping, rb, x, log2_bs, lg, K, rows, 0, lane);
         for (int64_t it = 0;;) {
-            if (it + 1 < steps) load_step<B, CH, R, FULL>(pong, rb, x, log2_bs, K, rows, (it + 1) * kSlice, lane);
+            if (it + 1 < steps) load_step<B, CH, R, FULL>(pong, rb, x, log2_bs, lg, K, rows, (it + 1) * kSlice, lane);
             compute_step_pair<B, CH, R>(ping, smem, lane_off, code2_lds, offset, acc);
             if (++it >= steps) break;
-            if (it + 1 < steps) load_step<B, CH, R, FULL>(ping, rb, x, log2_bs, K, rows, (it + 1) * kSlice, lane);
+            if (it + 1 < steps) load_step<B, CH, R, FULL>(ping, rb, x, log2_bs, lg, K, rows, (it + 1) * kSlice, lane);
             compute_step_pair<B, CH, R>(pong, smem, lane_off, code2_lds, offset, acc);
             if (++it >= steps) break;
         }
@@ -445,44 +447,47 @@ __global__ __launch_bounds__(kPairWaves * kWave) void gemv_pair_kernel(const uin
 
 template <int B, int CH, int R>
 static void launch_gemv(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
-                        const float* code2, int log2_bs, int64_t N, int64_t K, const void* x, void* y,
+                        const float* code2, int log2_bs, Fmt fmt, int64_t N, int64_t K, const void* x, void* y,
                         hipStream_t s) {
     if (K >= kPairMinK) {
         const unsigned pair_groups = (unsigned)((N + R * kPairWaves - 1) / (R * kPairWaves));
         if constexpr ((CH == 4 || CH == 2) && R == 4) {
             // whole steps, block size 64, the scale codes loadable in pairs: the two-load scale fetch
+            // (two neighbouring blocks share a second-level scale: groups of at least two blocks; taken for 256)
             if (K % (8 * CH * kWave) == 0 && N % R == 0 && log2_bs == 6 && aligned(q8, 2) && K % 128 == 0 &&
-                K < (int64_t(1) << 31)) {
+                K < (int64_t(1) << 31) && fmt.log2_group == 8) {
                 hipLaunchKernelGGL((gemv_pair_kernel<B, CH, R, true, true>), dim3(pair_groups),
-                                   dim3(kPairWaves * kWave), 0, s, packed, q8, scale2, offset, code2, log2_bs, N, K,
-                                   (const _Float16*)x, (_Float16*)y);
+                                   dim3(kPairWaves * kWave), 0, s, packed, q8, scale2, offset, code2, log2_bs, fmt,
+                                   N, K, (const _Float16*)x, (_Float16*)y);
                 return;
             }
         }
         if (K % (8 * CH * kWave) == 0 && N % R == 0)
             hipLaunchKernelGGL((gemv_pair_kernel<B, CH, R, true>), dim3(pair_groups), dim3(kPairWaves * kWave), 0, s,
-                               packed, q8, scale2, offset, code2, log2_bs, N, K, (const _Float16*)x, (_Float16*)y);
+                               packed, q8, scale2, offset, code2, log2_bs, fmt, N, K, (const _Float16*)x,
+                               (_Float16*)y);
         else
             hipLaunchKernelGGL((gemv_pair_kernel<B, CH, R, false>), dim3(pair_groups), dim3(kPairWaves * kWave), 0,
-                               s, packed, q8, scale2, offset, code2, log2_bs, N, K, (const _Float16*)x,
+                               s, packed, q8, scale2, offset, code2, log2_bs, fmt, N, K, (const _Float16*)x,
                                (_Float16*)y);
         return;
     }
     const unsigned groups = (unsigned)((N + R - 1) / R);
     if (K % (8 * CH * kWave) == 0 && N % R == 0)
         hipLaunchKernelGGL((gemv_kernel<B, CH, R, true>), dim3(groups), dim3(kWave), 0, s, packed, q8, scale2,
-                           offset, code2, log2_bs, N, K, (const _Float16*)x, (_Float16*)y);
+                           offset, code2, log2_bs, fmt, N, K, (const _Float16*)x, (_Float16*)y);
     else
         hipLaunchKernelGGL((gemv_kernel<B, CH, R, false>), dim3(groups), dim3(kWave), 0, s, packed, q8, scale2,
-                           offset, code2, log2_bs, N, K, (const _Float16*)x, (_Float16*)y);
+                           offset, code2, log2_bs, fmt, N, K, (const _Float16*)x, (_Float16*)y);
 }
 
 static int gemv_tokens(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
-                       const float* code2, int log2_bs, int64_t N, int64_t K, const _Float16* x, int B,
+                       const float* code2, int log2_bs, Fmt fmt, int64_t N, int64_t K, const _Float16* x, int B,
                        _Float16* y, hipStream_t s) {
-    if (gemv_slice_eligible(N, K, B)) return launch_gemv_slice(packed, q8, scale2, offset, code2, log2_bs, N, K, x, B, y, s);
+    if (gemv_slice_eligible(N, K, B))
+        return launch_gemv_slice(packed, q8, scale2, offset, code2, log2_bs, fmt, N, K, x, B, y, s);
 #define NF4_GEMV_CASE(b, ch, r) \
-    case b: launch_gemv<b, ch, r>(packed, q8, scale2, offset, code2, log2_bs, N, K, x, y, s); break;
+    case b: launch_gemv<b, ch, r>(packed, q8, scale2, offset, code2, log2_bs, fmt, N, K, x, y, s); break;
     switch (B) {
         // (tokens, code dwords per lane per row, rows per wave): picked by sweeping on MI355X
         NF4_GEMV_CASE(1, 4, 4) NF4_GEMV_CASE(2, 4, 4) NF4_GEMV_CASE(3, 2, 4) NF4_GEMV_CASE(4, 2, 4)
@@ -506,40 +511,61 @@ static int mfma_min_tokens(int64_t N) { return N < 16384 ? 3 : 5; }
 constexpr int kSplitMinTokens = 3;
 
 int launch_gemv_ws(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
-                   const float* code2, int log2_bs, int64_t N, int64_t K, const _Float16* x, int B, _Float16* y,
-                   float* partial, hipStream_t s) {
-    if (B < kSplitMinTokens) return gemv_tokens(packed, q8, scale2, offset, code2, log2_bs, N, K, x, B, y, s);
-    return launch_gemm_splitk(packed, q8, scale2, offset, code2, log2_bs, N, K, x, B, y, partial, true, s);
+                   const float* code2, int log2_bs, Fmt fmt, int64_t N, int64_t K, const _Float16* x, int B,
+                   _Float16* y, float* partial, hipStream_t s) {
+    if (B < kSplitMinTokens) return gemv_tokens(packed, q8, scale2, offset, code2, log2_bs, fmt, N, K, x, B, y, s);
+    return launch_gemm_splitk(packed, q8, scale2, offset, code2, log2_bs, fmt, N, K, x, B, y, partial, true, s);
+}
+
+// Argument checks shared by the GEMV entry points (everything but the workspace).
+static int check_gemv_args(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
+                           const float* code2, int blocksize, int64_t N, int64_t K, const void* x, int B,
+                           const void* y, const Fmt& fmt, int* log2_bs) {
+    if (N < 0 || K < 0) return NF4_ERR_SIZE;
+    *log2_bs = log2_blocksize(blocksize);
+    if (*log2_bs < 0) return NF4_ERR_BLOCKSIZE;
+    if (B < 1 || B > 16) return NF4_ERR_SHAPE;
+    if (fmt.log2_group < 0) return NF4_ERR_SHAPE;
+    if (N > 0 && (K <= 0 || K % blocksize != 0)) return NF4_ERR_SHAPE;   // blocksize is a multiple of 32
+    if (N > 0x7fffffffLL) return NF4_ERR_SIZE;
+    if (N == 0) return NF4_OK;
+    if (!packed || !q8 || !scale2 || !offset || !code2 || !x || !y) return NF4_ERR_NULL;
+    if (!aligned(packed, 16) || !aligned(x, 16) || !aligned(y, 2) || !aligned(scale2, 4) || !aligned(offset, 4) ||
+        !aligned(code2, 4) || !aligned(fmt.codebook, 4))
+        return NF4_ERR_ALIGN;
+    return NF4_OK;
+}
+
+// nf4_dequant_gemv / nf4_dequant_gemv_ws (workspace != nullptr) for any format.
+static int gemv_entry(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
+                      const float* code2, int blocksize, Fmt fmt, int64_t N, int64_t K, const void* x, int B,
+                      void* y, bool with_workspace, void* workspace, size_t workspace_bytes, void* stream) {
+    int log2_bs = 0;
+    const int rc = check_gemv_args(packed, q8, scale2, offset, code2, blocksize, N, K, x, B, y, fmt, &log2_bs);
+    if (rc != NF4_OK || N == 0) return rc;
+    hipStream_t s = (hipStream_t)stream;
+    if (with_workspace) {
+        if (!workspace) return NF4_ERR_NULL;
+        if (!aligned(workspace, 16)) return NF4_ERR_ALIGN;
+        if (workspace_bytes < nf4_dequant_gemv_workspace_bytes(N, K, B)) return NF4_ERR_SIZE;
+        return launch_gemv_ws(packed, q8, scale2, offset, code2, log2_bs, fmt, N, K, (const _Float16*)x, B,
+                              (_Float16*)y, (float*)workspace, s);
+    }
+    // From mfma_min_tokens tokens on the sum goes to the matrix cores: the levels enter them as two FP16 terms
+    // (22 significant bits), the activations as they are, the block scale multiplies each block's partial sums in
+    // FP32, accumulation in FP32.  Below that, FMAs on the vector ALU with the FP32 weight never narrowed.
+    if (B >= mfma_min_tokens(N))
+        return launch_gemv_mfma(packed, q8, scale2, offset, code2, log2_bs, fmt, N, K, (const _Float16*)x, B,
+                                (_Float16*)y, s);
+    return gemv_tokens(packed, q8, scale2, offset, code2, log2_bs, fmt, N, K, (const _Float16*)x, B, (_Float16*)y, s);
 }
 }
 
 extern "C" int nf4_dequant_gemv(const uint8_t* packed, const uint8_t* absmax_q8, const float* scale2,
                                 const float* offset, const float* code2, int blocksize, int64_t N,
                                 int64_t K, const void* x, int B, void* y, void* stream) {
-    using namespace nf4;
-    if (N < 0 || K < 0) return NF4_ERR_SIZE;
-    const int log2_bs = log2_blocksize(blocksize);
-    if (log2_bs < 0) return NF4_ERR_BLOCKSIZE;
-    if (B < 1 || B > 16) return NF4_ERR_SHAPE;
-    if (N > 0 && (K <= 0 || K % blocksize != 0)) return NF4_ERR_SHAPE;   // blocksize is a multiple of 32
-    if (N > 0x7fffffffLL) return NF4_ERR_SIZE;
-    if (N == 0) return NF4_OK;
-    if (!y) return NF4_ERR_NULL;
-    if (!aligned(y, 2)) return NF4_ERR_ALIGN;
-    hipStream_t s = (hipStream_t)stream;
-    if (!packed || !absmax_q8 || !scale2 || !offset || !code2 || !x) return NF4_ERR_NULL;
-    if (!aligned(packed, 16) || !aligned(x, 16) || !aligned(scale2, 4) || !aligned(offset, 4) ||
-        !aligned(code2, 4))
-        return NF4_ERR_ALIGN;
-
-    // From mfma_min_tokens tokens on the sum goes to the matrix cores: the levels enter them as two FP16 terms
-    // (22 significant bits), the activations as they are, the block scale multiplies each block's partial sums in
-    // FP32, accumulation in FP32.  Below that, FMAs on the vector ALU with the FP32 weight never narrowed.
-    if (B >= mfma_min_tokens(N))
-        return launch_gemv_mfma(packed, absmax_q8, scale2, offset, code2, log2_bs, N, K, (const _Float16*)x, B,
-                                (_Float16*)y, s);
-    return gemv_tokens(packed, absmax_q8, scale2, offset, code2, log2_bs, N, K, (const _Float16*)x, B,
-                       (_Float16*)y, s);
+    return nf4::gemv_entry(packed, absmax_q8, scale2, offset, code2, blocksize, nf4::kNf4Fmt, N, K, x, B, y, false,
+                           nullptr, 0, stream);
 }
 
 // ---- the same sum with a caller workspace: from kSplitMinTokens tokens on K is split across workgroups (the
@@ -554,19 +580,16 @@ extern "C" int nf4_dequant_gemv_ws(const uint8_t* packed, const uint8_t* absmax_
                                    const float* offset, const float* code2, int blocksize, int64_t N, int64_t K,
                                    const void* x, int B, void* y, void* workspace, size_t workspace_bytes,
                                    void* stream) {
-    using namespace nf4;
-    if (N < 0 || K < 0) return NF4_ERR_SIZE;
-    const int log2_bs = log2_blocksize(blocksize);
-    if (log2_bs < 0) return NF4_ERR_BLOCKSIZE;
-    if (B < 1 || B > 16) return NF4_ERR_SHAPE;
-    if (N > 0 && (K <= 0 || K % blocksize != 0)) return NF4_ERR_SHAPE;
-    if (N > 0x7fffffffLL) return NF4_ERR_SIZE;
-    if (N == 0) return NF4_OK;
-    if (!packed || !absmax_q8 || !scale2 || !offset || !code2 || !x || !y || !workspace) return NF4_ERR_NULL;
-    if (!aligned(packed, 16) || !aligned(x, 16) || !aligned(y, 2) || !aligned(scale2, 4) || !aligned(offset, 4) ||
-        !aligned(code2, 4) || !aligned(workspace, 16))
-        return NF4_ERR_ALIGN;
-    if (workspace_bytes < nf4_dequant_gemv_workspace_bytes(N, K, B)) return NF4_ERR_SIZE;
-    return launch_gemv_ws(packed, absmax_q8, scale2, offset, code2, log2_bs, N, K, (const _Float16*)x, B,
-                          (_Float16*)y, (float*)workspace, (hipStream_t)stream);
+    return nf4::gemv_entry(packed, absmax_q8, scale2, offset, code2, blocksize, nf4::kNf4Fmt, N, K, x, B, y, true,
+                           workspace, workspace_bytes, stream);
+}
+
+// ---- the data type as a parameter (Sec. V-A): the same two calls for any 16 levels and second-level group size
+extern "C" int nf4_dequant_gemv_codebook(const uint8_t* packed, const uint8_t* absmax_q8, const float* scale2,
+                                         const float* offset, const float* code2, int dq_group,
+                                         const float* codebook, int blocksize, int64_t N, int64_t K, const void* x,
+                                         int B, void* y, void* workspace, size_t workspace_bytes, void* stream) {
+    const nf4::Fmt fmt = {nf4::log2_dq_group(dq_group), codebook};
+    return nf4::gemv_entry(packed, absmax_q8, scale2, offset, code2, blocksize, fmt, N, K, x, B, y,
+                           workspace != nullptr, workspace, workspace_bytes, stream);
 }

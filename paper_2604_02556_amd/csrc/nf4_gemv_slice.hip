@@ -54,7 +54,7 @@ __device__ __forceinline__ float reduce_four_rows(const float (&p)[4], int lane)
 template <bool FULL>
 __global__ __launch_bounds__(kSliceMaxWaves * kWave) void gemv_slice_kernel(
     const uint8_t* __restrict__ packed, const uint8_t* __restrict__ q8, const float* __restrict__ scale2,
-    const float* __restrict__ offset_p, const float* __restrict__ code2, int log2_bs, int64_t N, int64_t K,
+    const float* __restrict__ offset_p, const float* __restrict__ code2, int log2_bs, Fmt fmt, int64_t N, int64_t K,
     const _Float16* __restrict__ x, _Float16* __restrict__ y, int KS, int RS, int rows_per_wg) {
     // one LDS object, so that the pair table sits at address 0:
     // table | 16 levels | code2 | reduction buffer | block scales of the workgroup's rows
@@ -122,7 +122,8 @@ __global__ __launch_bounds__(kSliceMaxWaves * kWave) void gemv_slice_kernel(
         }
     }
 
-    if (tid < 16) lut[tid] = __uint_as_float(level_literal(tid));
+    const int lg = fmt.log2_group;
+    if (tid < 16) lut[tid] = fmt.codebook ? fmt.codebook[tid] : __uint_as_float(level_literal(tid));
     for (int i = tid; i < 256; i += threads) code2_lds[i] = code2[i];
     __syncthreads();
     fill_pair_table((float2_t*)smem, lut, tid, threads);
@@ -152,20 +153,21 @@ __global__ __launch_bounds__(kSliceMaxWaves * kWave) void gemv_slice_kernel(
 #pragma unroll
                     for (int j = 0; j < 4; ++j) c[t] |= (uint32_t)q8w[i + j < nblk ? i + j : nblk - 1] << (8 * j);
                 }
-                // four consecutive blocks touch at most two second-level groups (a group is 256 blocks)
-                s2a[t] = scale2[(b_begin + i) >> 8];
-                s2b[t] = scale2[(b_begin + (i + 3 < nblk ? i + 3 : nblk - 1)) >> 8];
+                // (with four or more blocks per second-level scale, four consecutive blocks touch at most two groups)
+                s2a[t] = scale2[(b_begin + i) >> lg];
+                s2b[t] = scale2[(b_begin + (i + 3 < nblk ? i + 3 : nblk - 1)) >> lg];
             }
         }
 #pragma unroll
         for (int t = 0; t < kTurns; ++t) {
             const int i = i0 + 4 * t * threads;
             if (i >= nblk) continue;
-            const int64_t g_first = (b_begin + i) >> 8;
+            const int64_t g_first = (b_begin + i) >> lg;
             f32x4 v;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const float s2 = ((b_begin + i + j) >> 8) == g_first ? s2a[t] : s2b[t];
+                float s2 = ((b_begin + i + j) >> lg) == g_first ? s2a[t] : s2b[t];
+                if (lg < 2) s2 = scale2[(b_begin + (i + j < nblk ? i + j : nblk - 1)) >> lg];   // groups of one or two blocks
                 const float prod = code2_lds[(c[t] >> (8 * j)) & 0xffu] * s2;      // rounded product, then rounded sum
                 v[j] = prod + offset;
             }
@@ -258,8 +260,8 @@ bool gemv_slice_eligible(int64_t N, int64_t K, int B) {
 }
 
 int launch_gemv_slice(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
-                      const float* code2, int log2_bs, int64_t N, int64_t K, const _Float16* x, int B, _Float16* y,
-                      hipStream_t s) {
+                      const float* code2, int log2_bs, Fmt fmt, int64_t N, int64_t K, const _Float16* x, int B,
+                      _Float16* y, hipStream_t s) {
     const int KS = (int)((K + kSliceElems - 1) / kSliceElems);
     const int RS = kSliceMaxWaves / KS;
     const int64_t G = compute_units();
@@ -275,7 +277,7 @@ int launch_gemv_slice(const uint8_t* packed, const uint8_t* q8, const float* sca
     const bool full = K % kSliceElems == 0;
 #define NF4_SLICE_LAUNCH(FULL_)                                                                            \
     hipLaunchKernelGGL((gemv_slice_kernel<FULL_>), grid, block, 0, s, packed, q8, scale2, offset, code2, log2_bs, \
-                       N, K, x, y, KS, RS, (int)rows)
+                       fmt, N, K, x, y, KS, RS, (int)rows)
     if (B != 1) return NF4_ERR_SHAPE;                              // gemv_slice_eligible
     if (full) NF4_SLICE_LAUNCH(true);
     else NF4_SLICE_LAUNCH(false);

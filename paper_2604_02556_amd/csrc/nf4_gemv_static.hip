@@ -69,6 +69,6 @@ extern "C" int nf4_dequant_gemv_static(const uint8_t* packed, const uint8_t* abs
     if (!partial) return rc;
     // Every partial sum that the second kernel reads is written by the first one in the same call, so what the
     // previous call left in the array does not matter and nothing has to be cleared.
-    return launch_gemv_ws(packed, absmax_q8, scale2, offset, code2, log2_bs, N, K, (const _Float16*)x, B,
+    return launch_gemv_ws(packed, absmax_q8, scale2, offset, code2, log2_bs, kNf4Fmt, N, K, (const _Float16*)x, B,
                           (_Float16*)y, partial, (hipStream_t)stream);
 }

@@ -32,6 +32,14 @@ inline int log2_dq_group(int group) {
     return -1;
 }
 
+// The data type as a parameter (Sec. V-A) for the fused kernels: blocks per second-level scale as a shift, and the
+// caller's 16 levels (device) or nullptr for the NF4 literals.
+struct Fmt {
+    int log2_group;
+    const float* codebook;
+};
+constexpr Fmt kNf4Fmt = {8, nullptr};
+
 // Compute units of the current device (queried once per thread; 256 on MI355X).
 int compute_units();
 
@@ -47,25 +55,25 @@ SplitPlan plan_split(int64_t N, int64_t K, int B);
 // The GEMV's sum (FP32 weights: levels to 22 bits as two FP16 terms, FP32 block scales) on the matrix cores,
 // B <= 16 (nf4_gemm.hip).
 int launch_gemv_mfma(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
-                     const float* code2, int log2_bs, int64_t N, int64_t K, const _Float16* x, int B, _Float16* y,
-                     hipStream_t s);
+                     const float* code2, int log2_bs, Fmt fmt, int64_t N, int64_t K, const _Float16* x, int B,
+                     _Float16* y, hipStream_t s);
 
 // Split-K GEMM: `partial` holds plan.splits * B * N floats when plan.splits > 1.  gemv_weights (B <= 16): W is the
 // FP32 product level * scale (levels as two FP16 terms, FP32 block scales) instead of rne_fp16(level * scale).
 int launch_gemm_splitk(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
-                       const float* code2, int log2_bs, int64_t N, int64_t K, const _Float16* x, int B,
+                       const float* code2, int log2_bs, Fmt fmt, int64_t N, int64_t K, const _Float16* x, int B,
                        _Float16* y, float* partial, bool gemv_weights, hipStream_t s);
 
 // One and two tokens by column slices (nf4_gemv_slice.hip): which shapes it takes, and the launch.
 bool gemv_slice_eligible(int64_t N, int64_t K, int B);
 int launch_gemv_slice(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
-                      const float* code2, int log2_bs, int64_t N, int64_t K, const _Float16* x, int B, _Float16* y,
-                      hipStream_t s);
+                      const float* code2, int log2_bs, Fmt fmt, int64_t N, int64_t K, const _Float16* x, int B,
+                      _Float16* y, hipStream_t s);
 
 // nf4_dequant_gemv_ws after its argument checks: FMA kernels for one and two tokens, split-K on the matrix cores
 // with `partial` (plan_split(N, K, B).splits * B * N floats, written before they are read) above that.
 int launch_gemv_ws(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
-                   const float* code2, int log2_bs, int64_t N, int64_t K, const _Float16* x, int B, _Float16* y,
-                   float* partial, hipStream_t s);
+                   const float* code2, int log2_bs, Fmt fmt, int64_t N, int64_t K, const _Float16* x, int B,
+                   _Float16* y, float* partial, hipStream_t s);
 
 }  // namespace nf4
