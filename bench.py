@@ -458,7 +458,7 @@ def leg_quantize(torch, nf4, synth, stream, gen, src):
     res = {"elements": n, "us": round(us, 2), "GB/s": round(bytes_ / (us * 1e-6) / 1e9, 1),
            "frac_of_hbm_peak": round(bytes_ / (us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
            "reference_quantizer_us": round(us_ref, 2), "dq_encode_us": round(us_dq, 2), "other_block_sizes": {}}
-    for bs in (128, 512, 2048):
+    for bs in (128, 512, 2048, 4096):
         bb = nf4.alloc_quantized(n, bs, device=src.device)
         t = time_on_stream(torch, stream, lambda: nf4.nf4_quantize(w, n, bs, bb["packed"], bb["absmax"], stream=stream), 10)
         by = n * (4.0 + 0.5 + 4.0 / bs)

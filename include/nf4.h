@@ -276,8 +276,8 @@ int nf4_quantize_ref_codebook(const float* src, int64_t n, int blocksize, const 
 /*
  * Tuned quantiser, first level only (Sec. II-B, forward direction): writes
  * exactly the packed[] and absmax[] that nf4_quantize_ref writes, bit for bit,
- * at HBM speed for blocksize 64 (other block sizes and the ragged end of a
- * tensor run through the reference kernel).  src must be 16-byte aligned,
+ * at HBM speed for every block size and any n (the tile that n does not fill is
+ * handled by predication inside the same kernel).  src must be 16-byte aligned,
  * packed 2-byte aligned.  The first call on a process builds a 512-byte table
  * on the host (no device allocation).
  */

@@ -1,4 +1,4 @@
-// Tuned NF4 quantiser for gfx950 (block sizes 64 to 2048): the forward direction of
+// Tuned NF4 quantiser for gfx950 (every block size, 64 to 4096; any n): the forward direction of
 // Sec. II-B, bit-identical to the reference quantiser (and so to the CPU
 // definition), at HBM speed.
 //
@@ -23,8 +23,8 @@
 // one DPP row (4 elements each), so its absmax is 3 in-lane and 4 DPP max
 // operations and needs no LDS; larger blocks add one or two cross-row exchanges
 // (ds_bpermute) and, from 512 on, a maximum over 2, 4 or 8 of the lane's own
-// loads; codes leave as eight 2-byte stores per lane, each instruction writing
-// one full 128-byte line.
+// loads, and for 4096 a maximum over the two waves of a workgroup; codes leave as
+// eight 2-byte stores per lane, each instruction writing one full 128-byte line.
 #include <math.h>
 #include <string.h>
 
@@ -139,18 +139,25 @@ __device__ __forceinline__ float max_across_rows(float a, int lane, bool all_fou
     return a;
 }
 
-// LOG2BS = log2(blocksize), 6..11: a block is one DPP row of one load (64), two or four rows of one load
-// (128, 256), or the whole wave over 2, 4 or 8 consecutive loads (512, 1024, 2048).
+// LOG2BS = log2(blocksize), 6..12: a block is one DPP row of one load (64), two or four rows of one load
+// (128, 256), the whole wave over 2, 4 or 8 consecutive loads (512, 1024, 2048), or the two waves of a workgroup
+// (4096: each wave reduces its tile, the two maxima meet in LDS).
+// A wave whose tile lies wholly inside the tensor takes the unpredicated path; the one tile that does not (Sec. V-A:
+// sizes that do not fill a tile) loads element by element with zeros past n -- which neither raise a block's
+// maximum nor, as x / absmax = 0, give anything but the zero level's code to the unused nibble of an odd n -- and
+// stores only the bytes and scales that exist.
 template <int LOG2BS>
-__global__ __launch_bounds__(kWave) void quantize_tiles_kernel(const float* __restrict__ src, QuantBins qb,
-                                                               uint8_t* __restrict__ packed,
-                                                               float* __restrict__ absmax) {
-    constexpr int kLoadsPerBlock = LOG2BS <= 8 ? 1 : (1 << (LOG2BS - 8));
-    constexpr int kBlocksPerTile = kQTileElems >> LOG2BS;
+__global__ __launch_bounds__((LOG2BS == 12 ? 2 : 1) * kWave) void quantize_tiles_kernel(
+    const float* __restrict__ src, QuantBins qb, int64_t n, uint8_t* __restrict__ packed,
+    float* __restrict__ absmax) {
+    constexpr int kWaves = LOG2BS == 12 ? 2 : 1;
+    constexpr int kLoadsPerBlock = LOG2BS <= 8 ? 1 : (LOG2BS >= 11 ? 8 : (1 << (LOG2BS - 8)));
     __shared__ float theta_lds[kBins];
     __shared__ uint32_t base_lds[kBins];
-    const int lane = threadIdx.x;
-    theta_lds[lane] = qb.theta[lane];
+    __shared__ float wave_max[2];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    theta_lds[lane] = qb.theta[lane];                    // (both waves of a 4096-block workgroup write the same values)
     base_lds[lane] = qb.base[lane];
     if (lane == 0) {
         theta_lds[kBins - 1] = qb.theta[kBins - 1];
@@ -158,11 +165,23 @@ __global__ __launch_bounds__(kWave) void quantize_tiles_kernel(const float* __re
     }
     wave_lds_fence();
 
-    const int64_t t = blockIdx.x;
-    const f32x4* in = (const f32x4*)(src + t * kQTileElems);
+    const int64_t t = (int64_t)blockIdx.x * kWaves + wave;
+    const int64_t e0 = t * kQTileElems;
+    const bool full = e0 + kQTileElems <= n;             // wave-uniform
     f32x4 v[8];
+    if (full) {
+        const f32x4* in = (const f32x4*)(src + e0);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) v[j] = __builtin_nontemporal_load(in + j * kWave + lane);
+        for (int j = 0; j < 8; ++j) v[j] = __builtin_nontemporal_load(in + j * kWave + lane);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int64_t i = e0 + 256 * j + 4 * lane + e;
+                v[j][e] = i < n ? src[i] : 0.0f;
+            }
+    }
 
     // ---- block maxima.  Lane holds elements 256 j + 4 lane .. + 3 of the tile.
     float a[8];
@@ -194,15 +213,24 @@ __global__ __launch_bounds__(kWave) void quantize_tiles_kernel(const float* __re
             for (int i = 0; i < kLoadsPerBlock; ++i) a[j + i] = m;
         }
     }
-    float* amax_tile = absmax + t * kBlocksPerTile;
+    if constexpr (LOG2BS == 12) {                        // the block is the workgroup's two tiles
+        if (lane == 0) wave_max[wave] = a[0];
+        __syncthreads();                                 // both waves always get here: there is no early exit
+        const float m = __builtin_fmaxf(wave_max[0], wave_max[1]);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) a[j] = m;
+    }
 #pragma unroll
     for (int j = 0; j < 8; j += kLoadsPerBlock) {
-        // first lane of each block writes its scale; block of element 256 j + 4 lane
+        // first lane of each block writes its scale; block of element e0 + 256 j + 4 lane
         const int first_lane_mask = LOG2BS >= 8 ? 63 : ((1 << (LOG2BS - 2)) - 1);
-        if ((lane & first_lane_mask) == 0) amax_tile[(256 * j + 4 * lane) >> LOG2BS] = a[j];
+        const int64_t first = e0 + 256 * j + 4 * lane;
+        const bool writer = (lane & first_lane_mask) == 0 && (LOG2BS < 12 || wave == 0);
+        if (writer && (full || first < n)) absmax[first >> LOG2BS] = a[j];
     }
 
-    uint16_t* out16 = (uint16_t*)(packed + t * (kQTileElems / 2));
+    uint16_t* out16 = (uint16_t*)(packed + (e0 >> 1));
+    const int64_t nbytes = (n + 1) >> 1;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         const float aj = a[j];
@@ -225,15 +253,25 @@ __global__ __launch_bounds__(kWave) void quantize_tiles_kernel(const float* __re
         }
         // element 2i in the high nibble of byte i; two bytes per lane, little-endian
         const uint32_t two_bytes = (code[0] << 4) | code[1] | (code[2] << 12) | (code[3] << 8);
-        __builtin_nontemporal_store((uint16_t)two_bytes, out16 + j * 64 + lane);   // bytes 128 j + 2 lane
+        if (full) {
+            __builtin_nontemporal_store((uint16_t)two_bytes, out16 + j * 64 + lane);   // bytes 128 j + 2 lane
+        } else {
+            const int64_t byte0 = (e0 >> 1) + 128 * j + 2 * lane;
+            if (byte0 + 1 < nbytes) out16[j * 64 + lane] = (uint16_t)two_bytes;
+            else if (byte0 < nbytes) packed[byte0] = (uint8_t)two_bytes;
+        }
     }
 }
 
 template <int LOG2BS>
-static int launch_tiles(const float* src, const QuantBins& qb, int64_t tiles, uint8_t* packed, float* absmax,
+static int launch_tiles(const float* src, const QuantBins& qb, int64_t n, uint8_t* packed, float* absmax,
                         hipStream_t s) {
-    hipLaunchKernelGGL(quantize_tiles_kernel<LOG2BS>, dim3((unsigned)tiles), dim3(kWave), 0, s, src, qb, packed,
-                       absmax);
+    constexpr int kWaves = LOG2BS == 12 ? 2 : 1;
+    const int64_t per_group = (int64_t)kWaves * kQTileElems;
+    const int64_t groups = (n + per_group - 1) / per_group;
+    if (groups > 0x7fffffffLL) return NF4_ERR_SIZE;
+    hipLaunchKernelGGL(quantize_tiles_kernel<LOG2BS>, dim3((unsigned)groups), dim3(kWaves * kWave), 0, s, src, qb, n,
+                       packed, absmax);
     return record_hip(hipGetLastError());
 }
 
@@ -254,25 +292,14 @@ extern "C" int nf4_quantize(const float* src, int64_t n, int blocksize, uint8_t*
     hipStream_t s = (hipStream_t)stream;
     const QuantBins* qb = quant_bins();
     const int log2_bs = log2_blocksize(blocksize);
-    // a block of 4096 does not fit the 2048-element tile of a wave: the reference kernel does those
-    if (log2_bs > 11 || qb == nullptr) return launch_quantize_ref_range(src, n, blocksize, nullptr, packed, absmax, s);
-
-    const int64_t tiles = n / kQTileElems;
-    if (tiles > 0x7fffffffLL) return NF4_ERR_SIZE;
-    if (tiles > 0) {
-        int rc = NF4_OK;
-        switch (log2_bs) {
-            case 6: rc = launch_tiles<6>(src, *qb, tiles, packed, absmax, s); break;
-            case 7: rc = launch_tiles<7>(src, *qb, tiles, packed, absmax, s); break;
-            case 8: rc = launch_tiles<8>(src, *qb, tiles, packed, absmax, s); break;
-            case 9: rc = launch_tiles<9>(src, *qb, tiles, packed, absmax, s); break;
-            case 10: rc = launch_tiles<10>(src, *qb, tiles, packed, absmax, s); break;
-            default: rc = launch_tiles<11>(src, *qb, tiles, packed, absmax, s); break;
-        }
-        if (rc != NF4_OK) return rc;
+    if (qb == nullptr) return launch_quantize_ref_range(src, n, blocksize, nullptr, packed, absmax, s);
+    switch (log2_bs) {
+        case 6: return launch_tiles<6>(src, *qb, n, packed, absmax, s);
+        case 7: return launch_tiles<7>(src, *qb, n, packed, absmax, s);
+        case 8: return launch_tiles<8>(src, *qb, n, packed, absmax, s);
+        case 9: return launch_tiles<9>(src, *qb, n, packed, absmax, s);
+        case 10: return launch_tiles<10>(src, *qb, n, packed, absmax, s);
+        case 11: return launch_tiles<11>(src, *qb, n, packed, absmax, s);
+        default: return launch_tiles<12>(src, *qb, n, packed, absmax, s);
     }
-    const int64_t done = tiles * kQTileElems;               // a multiple of every block size up to 2048
-    if (done == n) return NF4_OK;
-    return launch_quantize_ref_range(src + done, n - done, blocksize, nullptr, packed + done / 2,
-                                     absmax + (done >> log2_bs), s);
 }

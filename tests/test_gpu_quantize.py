@@ -109,7 +109,7 @@ def test_zero_blocks_exact_levels_and_extremes():
 
 
 @pytest.mark.parametrize("blocksize", [128, 4096])
-def test_other_blocksizes_go_through_the_reference_path(blocksize):
+def test_other_blocksizes_with_a_ragged_end(blocksize):
     w = synth.gaussian_weights(4096 * 5 + 300, 0.02, blocksize)
     p, a = oracle.quantize(w, blocksize)
     gp, ga = quantize_gpu(w, blocksize)
@@ -133,8 +133,8 @@ def test_tuned_equals_reference_on_a_70b_gate_projection():
 @pytest.mark.parametrize("blocksize", [128, 256, 512, 1024, 2048, 4096])
 @pytest.mark.parametrize("n", [2048 * 37, 2048 * 5 + 4096 + 17, 2048, 100])
 def test_other_block_sizes_match_the_oracle(blocksize, n):
-    """Blocks of 128 to 2048 run in the tuned kernel (cross-row and cross-load maxima), 4096 and ragged ends
-    in the reference kernel; codes and scales are the oracle's either way."""
+    """Blocks of 128 to 4096 in the tuned kernel (cross-row, cross-load and, for 4096, cross-wave maxima), ragged
+    ends included; codes and scales are the oracle's."""
     w = synth.gaussian_weights(n, 0.02, seed=blocksize + n % 101, outlier_p=0.002)
     w[2048:2048 + 64] = 0.0                                  # zeros inside a larger block
     if n >= 2048 * 5:
@@ -167,3 +167,23 @@ def test_tuned_quantiser_followed_by_the_second_level_equals_the_oracle(n, group
     assert np.array_equal(g["scale2"][:s2.size].view(np.uint32), s2.view(np.uint32))
     assert g["offset"].view(np.uint32)[0] == off.view(np.uint32)[0]
     assert np.array_equal(g["code2"].view(np.uint32), c2.view(np.uint32))
+
+
+@pytest.mark.parametrize("blocksize", [64, 128, 256, 512, 1024, 2048, 4096])
+@pytest.mark.parametrize("n", [1, 2, 3, 63, 65, 127, 2047, 2049, 4095, 4097, 6143, 8191, 8193, 2048 * 9 + 1031, 1_000_003])
+def test_ragged_sizes_write_nothing_past_the_end(n, blocksize):
+    """Sizes that do not fill a tile (Sec. V-A), for every block size: the predicated tile of the tuned kernel
+    gives the oracle's codes and scales -- a partial last block takes the maximum of the elements present, the
+    unused nibble of an odd n the zero level's code -- and leaves the bytes after packed[ceil(n/2) - 1] and
+    absmax[nb - 1] alone."""
+    w = synth.gaussian_weights(n, 0.02, seed=n + blocksize, outlier_p=0.002)
+    p, a = oracle.quantize(w, blocksize)
+    guard = 256
+    packed = torch.full((p.size + guard,), 0xCD, dtype=torch.uint8, device="cuda")
+    absmax = torch.full((a.size + guard,), -123.0, dtype=torch.float32, device="cuda")
+    nf4.nf4_quantize(dev(w), n, blocksize, packed, absmax)
+    torch.cuda.synchronize()
+    gp, ga = packed.cpu().numpy(), absmax.cpu().numpy()
+    assert np.array_equal(ga[:a.size].view(np.uint32), a.view(np.uint32))
+    assert np.array_equal(gp[:p.size], p)
+    assert np.all(gp[p.size:] == 0xCD) and np.all(ga[a.size:] == -123.0)
