@@ -151,7 +151,7 @@ __global__ __launch_bounds__((LOG2BS == 12 ? 2 : 1) * kWave) void quantize_tiles
     const float* __restrict__ src, QuantBins qb, int64_t n, uint8_t* __restrict__ packed,
     float* __restrict__ absmax) {
     constexpr int kWaves = LOG2BS == 12 ? 2 : 1;
-    constexpr int kLoadsPerBlock = LOG2BS <= 8 ? 1 : (LOG2BS >= 11 ? 8 : (1 << (LOG2BS - 8)));
+    constexpr int kLoadsPerBlock = LOG2BS >= 11 ? 8 : (1 << (LOG2BS > 8 ? LOG2BS - 8 : 0));
     __shared__ float theta_lds[kBins];
     __shared__ uint32_t base_lds[kBins];
     __shared__ float wave_max[2];
