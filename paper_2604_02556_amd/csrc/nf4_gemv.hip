@@ -484,7 +484,7 @@ static void launch_gemv(const uint8_t* packed, const uint8_t* q8, const float* s
 static int gemv_tokens(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
                        const float* code2, int log2_bs, Fmt fmt, int64_t N, int64_t K, const _Float16* x, int B,
                        _Float16* y, hipStream_t s) {
-    if (gemv_slice_eligible(N, K, B))
+    if (gemv_slice_eligible(N, K, B, fmt))
         return launch_gemv_slice(packed, q8, scale2, offset, code2, log2_bs, fmt, N, K, x, B, y, s);
 #define NF4_GEMV_CASE(b, ch, r) \
     case b: launch_gemv<b, ch, r>(packed, q8, scale2, offset, code2, log2_bs, fmt, N, K, x, y, s); break;

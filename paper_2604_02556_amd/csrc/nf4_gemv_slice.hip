@@ -153,7 +153,8 @@ __global__ __launch_bounds__(kSliceMaxWaves * kWave) void gemv_slice_kernel(
 #pragma unroll
                     for (int j = 0; j < 4; ++j) c[t] |= (uint32_t)q8w[i + j < nblk ? i + j : nblk - 1] << (8 * j);
                 }
-                // (with four or more blocks per second-level scale, four consecutive blocks touch at most two groups)
+                // (four or more blocks per second-level scale -- gemv_slice_eligible -- so that four consecutive blocks
+                // touch at most two groups)
                 s2a[t] = scale2[(b_begin + i) >> lg];
                 s2b[t] = scale2[(b_begin + (i + 3 < nblk ? i + 3 : nblk - 1)) >> lg];
             }
@@ -166,8 +167,7 @@ __global__ __launch_bounds__(kSliceMaxWaves * kWave) void gemv_slice_kernel(
             f32x4 v;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                float s2 = ((b_begin + i + j) >> lg) == g_first ? s2a[t] : s2b[t];
-                if (lg < 2) s2 = scale2[(b_begin + (i + j < nblk ? i + j : nblk - 1)) >> lg];   // groups of one or two blocks
+                const float s2 = ((b_begin + i + j) >> lg) == g_first ? s2a[t] : s2b[t];
                 const float prod = code2_lds[(c[t] >> (8 * j)) & 0xffu] * s2;      // rounded product, then rounded sum
                 v[j] = prod + offset;
             }
@@ -254,9 +254,12 @@ __global__ __launch_bounds__(kSliceMaxWaves * kWave) void gemv_slice_kernel(
 
 // Shapes the column-slice kernel takes: one token (for two, the 64 activations of a lane do not fit the registers of
 // a 16-wave workgroup beside the lookup pipeline: the kernel spills and is slower than the row-owning one), rows
-// long enough to fill a few slices and short enough for one workgroup to cover K.
-bool gemv_slice_eligible(int64_t N, int64_t K, int B) {
-    return B == 1 && N >= 1 && K >= 4096 && K <= (int64_t)kSliceMaxWaves * kSliceElems;
+// long enough to fill a few slices and short enough for one workgroup to cover K, second-level groups of at least
+// four blocks (the decoder of the scales fetches two second-level scales per four blocks; a per-block fetch behind
+// a test of the group size put the decoder's registers into scratch memory, and a kernel that uses any scratch
+// memory at all measured 5 us slower).
+bool gemv_slice_eligible(int64_t N, int64_t K, int B, const Fmt& fmt) {
+    return B == 1 && N >= 1 && K >= 4096 && K <= (int64_t)kSliceMaxWaves * kSliceElems && fmt.log2_group >= 2;
 }
 
 int launch_gemv_slice(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,

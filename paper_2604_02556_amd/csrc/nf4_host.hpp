@@ -65,7 +65,7 @@ int launch_gemm_splitk(const uint8_t* packed, const uint8_t* q8, const float* sc
                        _Float16* y, float* partial, bool gemv_weights, hipStream_t s);
 
 // One and two tokens by column slices (nf4_gemv_slice.hip): which shapes it takes, and the launch.
-bool gemv_slice_eligible(int64_t N, int64_t K, int B);
+bool gemv_slice_eligible(int64_t N, int64_t K, int B, const Fmt& fmt);
 int launch_gemv_slice(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
                       const float* code2, int log2_bs, Fmt fmt, int64_t N, int64_t K, const _Float16* x, int B,
                       _Float16* y, hipStream_t s);
