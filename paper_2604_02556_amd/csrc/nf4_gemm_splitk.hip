@@ -55,9 +55,11 @@ namespace nf4 {
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-// k per step: 512 for up to 32 tokens (256 bytes of codes per row and step: HBM likes that better than 128,
-// and half as many barriers), 256 above that (the activation tiles of 64 tokens would not fit twice in LDS).
-constexpr int window_of(int token_groups) { return token_groups <= 2 ? 512 : 256; }
+// k per step: 512 for up to 16 tokens (256 bytes of codes per row and step: HBM likes that better than 128,
+// and half as many barriers), 256 above that: with two token groups the 512-wide window spilled six registers, and
+// a kernel that touches scratch memory at all costs about 4 us per launch (32 tokens: 54 -> 50 us with the narrower
+// window and no spill); the activation tiles of 64 tokens would not fit twice in LDS anyway.
+constexpr int window_of(int token_groups) { return token_groups <= 1 ? 512 : 256; }
 
 template <int TG, int RG, int W, int WIN, bool SPLIT>
 __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* __restrict__ packed,
