@@ -4,14 +4,16 @@
 // (Sec. IV-B: staged from constant memory into shared memory by thread 0;
 // Sec. III-B: the baseline re-reads it from global memory).  On CDNA4 that is
 // an open question, answered here by measurement.  Every variant below is the
-// library's dequantisation kernel -- same tile, same 128-bit loads, same LDS
-// lane exchange, same non-temporal 128-bit stores -- and differs ONLY in how a
+// library's dequantisation kernel in its first form -- same tile, same 128-bit
+// loads, same LDS lane exchange, non-temporal 128-bit stores for every tensor
+// size (the library has since picked the stores' cache policy by output size,
+// which is independent of the table's placement) -- and differs ONLY in how a
 // 4-bit code becomes an FP32 level:
 //
 //   bpermute     level[lane mod 16] in a VGPR built from literals, read with
-//                ds_bpermute_b32 (the library's choice)
-//   lds16        16 floats in LDS written from literals by one lane per
-//                workgroup, read with ds_read_b32
+//                ds_bpermute_b32
+//   lds16        16 floats in LDS written from literals by the first 16 lanes
+//                of a workgroup, read with ds_read_b32 (the library's choice)
 //   lds16_const  the paper's design transplanted: table in constant memory,
 //                one lane copies it to LDS, barrier, ds_read_b32
 //   lds256       256-entry byte -> (level[hi], level[lo]) table in LDS (2 KiB),
