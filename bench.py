@@ -18,8 +18,9 @@ Prints ONE JSON line.  `value` is algorithmic GB/s over the timed steps with
 every input already in HBM.  `roofline` prices the dequantisation kernel
 against the 8 TB/s HBM peak using HIP events on the launch stream;
 `cpu_baseline` times the plain CPU oracle on the first two layers of the same stream.
-Two short extra legs (double-quant BF16 on Gemma-27B shapes, the fused GEMV on
-the 70B MLP shapes) are reported under `extra`.
+Short extra legs (double-quant BF16 on Gemma-27B shapes, the fused GEMV and GEMM on
+the 70B MLP shapes, the tuned quantiser, other formats, a Qwen3-32B layer replay)
+are reported under `extra`.
 """
 import argparse
 import json
