@@ -146,18 +146,23 @@ __device__ __forceinline__ void dequant_group(const uint8_t* __restrict__ packed
             const int64_t b0 = e0 >> log2_bs;
             float mine = 0.0f;
             if constexpr (DQ) {
-                // Two round trips to memory, not three: the 8-bit code and the second-level scale are requested
-                // first, the codes right behind them (vector loads complete in order, so the wave can wait for the
-                // first two alone), and the dependent read of the code2 map goes out while the codes are in flight.
-                // For the largest tensors the codes wait for the first round trip, as in the FP32-scale form.
-                // (lanes past the tile's blocks repeat its first block: no predicated loads, whose results the
-                // compiler would have to wait for at the end of the predicated region)
+                // One round trip to memory: the 8-bit code, the second-level scale, the whole 1 KiB code2 map (one
+                // coalesced load, always a cache hit) and the codes are requested together; the map goes through
+                // the exchange buffer, which is free until the codes arrive, and the dependent lookup is an LDS read.
+                // (Reading code2[q] from memory once q had arrived made it two round trips: Gemma-27B leg 158 -> 155.5 us
+                // per layer; the straightforward order, three: 161.)  For the largest tensors the codes wait for the
+                // scale codes, as in the FP32-scale form.  Lanes past the tile's blocks repeat its first block: no
+                // predicated loads, whose results the compiler would have to wait for at the end of the predicated region.
                 const int64_t blk = b0 + (lane < per_tile ? lane : 0);
                 const uint32_t q = sa.q8[blk];
                 const float s2 = sa.scale2[blk >> sa.log2_group];
+                const u32x4 map = *(const u32x4*)(sa.code2 + 4 * lane);
                 if constexpr (CLS == kOutStream) asm volatile("" : "+v"(code_off) : "v"(q), "v"(s2));
                 codes = *(const u32x4*)(tile_codes + code_off);
-                const float prod = sa.code2[q] * s2;               // a rounded product, then a rounded sum (never an FMA)
+                *(u32x4*)&stage[4 * lane] = map;
+                wave_lds_fence();
+                const float prod = ((const float*)stage)[q] * s2;  // a rounded product, then a rounded sum (never an FMA)
+                wave_lds_fence();                                  // read before the codes overwrite the buffer
                 mine = prod + offset;
             } else {
                 if constexpr (CLS == kOutSmall) codes = *(const u32x4*)(tile_codes + code_off);

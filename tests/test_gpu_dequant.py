@@ -6,7 +6,8 @@ import torch
 
 import oracle
 from paper_2604_02556_amd import synth
-from gpu_util import (dequantize_dq_gpu, dequantize_gpu, guard_intact, mismatches)
+from paper_2604_02556_amd import binding as nf4
+from gpu_util import (bits, dequantize_dq_gpu, dequantize_gpu, dev, guard_intact, mismatches, out_buffer)
 
 pytestmark = pytest.mark.gpu
 
@@ -137,3 +138,21 @@ def test_double_quant_arbitrary_code_map_and_negative_scales():
     want = oracle.dequantize_dq(packed, q8, s2, off, code2, n, out_dtype=oracle.FP16)
     whole, got = dequantize_dq_gpu(packed, q8, s2, off, code2, n, torch.float16)
     assert np.array_equal(got, want) and guard_intact(whole, n)
+
+
+def test_double_quant_with_the_code2_map_at_a_4_byte_aligned_address():
+    """The interface asks for 4-byte alignment of the FP32 arrays; the kernel fetches the 256-entry map with 128-bit
+    loads, which must work from any such address."""
+    n = 2048 * 9 + 700
+    w = synth.gaussian_weights(n, 0.02, seed=91)
+    p, a = oracle.quantize(w)
+    q8, s2, off, c2 = oracle.dq_encode(a)
+    want = oracle.dequantize_dq(p, q8, s2, off, c2, n, out_dtype=oracle.BF16)
+    for shift in (1, 2, 3):
+        buf = torch.zeros(256 + 4, dtype=torch.float32, device="cuda")
+        buf[shift:shift + 256] = dev(c2)
+        whole, out = out_buffer(n, torch.bfloat16)
+        nf4.nf4_dequantize_dq(dev(p), dev(q8), dev(s2), dev(off), buf[shift:shift + 256], 64, n, out)
+        torch.cuda.synchronize()
+        assert mismatches(bits(out), want, bf16=True) == 0
+        assert guard_intact(whole, n)
