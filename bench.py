@@ -356,9 +356,12 @@ def gemv_entry(n, B, us, kernel):
 
 
 def gemv_kernel_name(N, K, B, workspace):
-    """Which kernel the entry points choose (nf4_gemv.hip: mfma_min_tokens, kSplitMinTokens; nf4_gemv_slice.hip)."""
+    """Which kernel the entry points choose (nf4_gemv.hip: mfma_min_tokens, kSplitMinTokens; nf4_gemv_slice.hip,
+    nf4_gemv_quad.hip)."""
     if B == 1 and 4096 <= K <= 32768:
         return "gemv_slice_kernel (FP32 FMAs, column slices)"
+    if B in (3, 4) and 4096 <= K <= 32768:
+        return "gemv_quad_kernel (4x4x4 matrix-core instruction, column pieces, levels as two FP16 terms)"
     if workspace and B >= 3:
         return "gemm_splitk_kernel<SPLIT> + gemm_reduce_kernel (matrix cores, levels as two FP16 terms)"
     if B >= (3 if N < 16384 else 5):

@@ -116,12 +116,14 @@ int nf4_dequantize_batch(const nf4_tensor* tensors, int count, int blocksize, in
  * FP32 accumulation, W is [N][K] row-major with double-quantised scales as in
  * nf4_dequantize_dq.  x : FP16 [B][K], y : FP16 [B][N], 1 <= B <= 16, K > 0
  * and K % blocksize == 0 (else NF4_ERR_SHAPE).  packed and x must be 16-byte
- * aligned.  For one or two tokens (up to four when N >= 16384) W stays the FP32
- * product (vector-ALU FMAs).  For more tokens the sum runs on the matrix cores:
- * every level enters them as two FP16 terms (the level to about 2^-22
- * relative), the products of a quantisation block are summed unscaled in FP32
- * and the block's FP32 scale multiplies that sum, so W is carried to about 22
- * significant bits whatever its magnitude.
+ * aligned.  For one and two tokens W stays the FP32 product (vector-ALU FMAs);
+ * so it does for three and four when N >= 16384 and K < 4096.  Otherwise the
+ * sum runs on the matrix cores (three and four tokens with K >= 4096: the
+ * 4 x 4 x 4 instruction, one column piece per lane; else 16-row tiles): every
+ * level enters them as two FP16 terms (the level to about 2^-22 relative), the
+ * products of a quantisation block are summed unscaled in FP32 and the block's
+ * FP32 scale multiplies that sum, so W is carried to about 22 significant bits
+ * whatever its magnitude.
  */
 int nf4_dequant_gemv(const uint8_t* packed, const uint8_t* absmax_q8, const float* scale2,
                      const float* offset, const float* code2, int blocksize, int64_t N,
@@ -132,11 +134,14 @@ int nf4_dequant_gemv(const uint8_t* packed, const uint8_t* absmax_q8, const floa
  * caller, contents undefined before and after; at least
  * nf4_dequant_gemv_workspace_bytes(N, K, B) bytes, else NF4_ERR_SIZE; NULL is
  * NF4_ERR_NULL).  Same definition of y, same arguments, layouts and limits.
- * From 3 tokens on, K is split across workgroups that share the activations
- * through LDS; FP32 partial sums go to the workspace and a second kernel adds
- * them in a fixed order (deterministic).  W is carried as on the matrix-core
- * path above (levels as two FP16 terms, FP32 block scales).  About 40 us for 3
- * to 16 tokens on the 70B MLP shapes, where nf4_dequant_gemv takes 41 to 70.
+ * One and two tokens run as in nf4_dequant_gemv, and so do three and four
+ * when K >= 4096 (the workspace is not touched).  From 5 tokens on (from 3
+ * when K < 4096), K is split across
+ * workgroups that share the activations through LDS; FP32 partial sums go to
+ * the workspace and a second kernel adds them in a fixed order
+ * (deterministic).  W is carried as on the matrix-core path above (levels as
+ * two FP16 terms, FP32 block scales).  About 42 us for 5 to 16 tokens on the
+ * 70B MLP shapes, where nf4_dequant_gemv takes 55 to 70.
  * Calls that share a workspace must not overlap.
  */
 int nf4_dequant_gemv_ws(const uint8_t* packed, const uint8_t* absmax_q8, const float* scale2,

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libnf4.so")
 SOURCES = ["nf4_api.hip", "nf4_dequant.hip", "nf4_gemv.hip", "nf4_quantize_ref.hip", "nf4_quantize.hip", "nf4_gemm.hip", "nf4_gemm_splitk.hip",
-           "nf4_gemv_static.hip", "nf4_gemv_slice.hip"]
+           "nf4_gemv_static.hip", "nf4_gemv_slice.hip", "nf4_gemv_quad.hip"]
 
 # -ffp-contract=off: every FP32 multiply and add is rounded on its own, as the
 # format's definition states (FMAs are written explicitly where wanted).

@@ -481,11 +481,22 @@ static void launch_gemv(const uint8_t* packed, const uint8_t* q8, const float* s
                            offset, code2, log2_bs, fmt, N, K, (const _Float16*)x, (_Float16*)y);
 }
 
+// Three and four tokens of a shape the 4 x 4 x 4 matrix-core kernel takes.  (One token is faster on the vector ALU;
+// two are within a tenth of it there, 37-40 us against 34, and keep the FP32 weight.)
+static bool gemv_quad_tokens(int64_t N, int64_t K, int B, int log2_bs, const Fmt& fmt) {
+    return B >= 3 && B <= 4 && gemv_quad_eligible(N, K, B, log2_bs, fmt);
+}
+
 static int gemv_tokens(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
                        const float* code2, int log2_bs, Fmt fmt, int64_t N, int64_t K, const _Float16* x, int B,
                        _Float16* y, hipStream_t s) {
+    // Column layouts first (rows of 4096 columns and more): one token on the vector ALU, three and four on the small
+    // matrix-core instruction (on the 70B MLP shapes 35-39 us, against 44-60 us for the row-owning kernels below
+    // and 42-45 us for the split-K kernel).
     if (gemv_slice_eligible(N, K, B, fmt))
         return launch_gemv_slice(packed, q8, scale2, offset, code2, log2_bs, fmt, N, K, x, B, y, s);
+    if (gemv_quad_tokens(N, K, B, log2_bs, fmt))
+        return launch_gemv_quad(packed, q8, scale2, offset, code2, log2_bs, fmt, N, K, x, B, y, s);
 #define NF4_GEMV_CASE(b, ch, r) \
     case b: launch_gemv<b, ch, r>(packed, q8, scale2, offset, code2, log2_bs, fmt, N, K, x, y, s); break;
     switch (B) {
@@ -513,7 +524,8 @@ constexpr int kSplitMinTokens = 3;
 int launch_gemv_ws(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
                    const float* code2, int log2_bs, Fmt fmt, int64_t N, int64_t K, const _Float16* x, int B,
                    _Float16* y, float* partial, hipStream_t s) {
-    if (B < kSplitMinTokens) return gemv_tokens(packed, q8, scale2, offset, code2, log2_bs, fmt, N, K, x, B, y, s);
+    if (B < kSplitMinTokens || gemv_quad_tokens(N, K, B, log2_bs, fmt))
+        return gemv_tokens(packed, q8, scale2, offset, code2, log2_bs, fmt, N, K, x, B, y, s);
     return launch_gemm_splitk(packed, q8, scale2, offset, code2, log2_bs, fmt, N, K, x, B, y, partial, true, s);
 }
 
@@ -554,7 +566,7 @@ static int gemv_entry(const uint8_t* packed, const uint8_t* q8, const float* sca
     // From mfma_min_tokens tokens on the sum goes to the matrix cores: the levels enter them as two FP16 terms
     // (22 significant bits), the activations as they are, the block scale multiplies each block's partial sums in
     // FP32, accumulation in FP32.  Below that, FMAs on the vector ALU with the FP32 weight never narrowed.
-    if (B >= mfma_min_tokens(N))
+    if (B >= mfma_min_tokens(N) && !gemv_quad_tokens(N, K, B, log2_bs, fmt))
         return launch_gemv_mfma(packed, q8, scale2, offset, code2, log2_bs, fmt, N, K, (const _Float16*)x, B,
                                 (_Float16*)y, s);
     return gemv_tokens(packed, q8, scale2, offset, code2, log2_bs, fmt, N, K, (const _Float16*)x, B, (_Float16*)y, s);

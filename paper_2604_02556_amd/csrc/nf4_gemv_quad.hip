@@ -1,0 +1,299 @@
+// Fused NF4 dequantise + decode GEMV for up to four tokens on the small matrix-core instruction
+// (v_mfma_f32_4x4x4_16B_f16: sixteen independent 4 x 4 x 4 products per wave), laid out by columns like the one-token
+// kernel of nf4_gemv_slice.hip.
+//
+// Why this instruction: its lane layout is the one a coalesced read of W wants.  Lane l belongs to block l / 4 and
+// supplies, as the B operand, four consecutive k of ONE weight row (row l % 4 of a group of four rows) and, as the A
+// operand, four consecutive k of ONE token (token l % 4); the result D[token][row] of a block lands in the lane of that
+// row, four tokens in four registers.  So
+//   * lane (c = l / 4, i = l % 4) loads the 16 bytes of codes of row i of the group at columns 32 c .. 32 c + 31 of
+//     the wave's 512 columns: a wave-load is 4 rows x 256 contiguous bytes, and the waves of a workgroup that share
+//     the rows read them side by side (the 16-row tiles of the big MFMA shapes would be 64 bytes per row);
+//   * the lane's 32 activations per token (token i, its own columns) stay in 16 registers for the whole pass over
+//     the rows: no activation traffic in the loop, nothing goes through LDS except the lookups;
+//   * a lane's 32 columns lie in one quantisation block and its results are those of its own row, so the block scale
+//     is applied by the lane that owns it, in FP32, to the four sums of eight 4-wide steps;
+//   * every level enters as two FP16 terms (the split table of nf4_device.hpp: hi + lo = the level to about 2^-22),
+//     two MFMAs per step, as on the other matrix-core paths of the GEMV; accumulation in FP32;
+//   * the cost does not depend on the number of tokens (1 to 4): 16 lookups, 16 permutes, 16 small MFMAs and about
+//     a dozen other vector instructions per 2048 weights, against 32 B multiply-adds on the vector ALU.
+// A workgroup is KSW column waves x RS row streams (at most 16 waves) and owns a contiguous range of rows; when K is
+// wider than its waves (more than 8192 columns) it passes over the rows once per group of columns, reloading the 16
+// activation registers, and adds into the same LDS slots.  Per (row, token) the sums of the sixteen 32-column pieces
+// of a wave meet by two DPP adds down to one per 16 lanes; those go to LDS and are added in a fixed order at the end
+// (deterministic).  Block scales are decoded once per workgroup into LDS as in the one-token kernel.
+#include "nf4_device.hpp"
+#include "nf4_host.hpp"
+
+namespace nf4 {
+
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kQuadCols = 512;               // columns per wave: 16 blocks of the MFMA x 32
+constexpr int kQuadRing = 4;                 // row groups whose codes a wave has in flight
+constexpr int kQuadMaxWaves = 16;
+constexpr int kQuadRedBytes = 32 * 1024;     // per row and slot (column wave x 16 lanes) one f32x4 of token sums
+constexpr int kQuadScaleFloats = 15360;      // decoded block scales of the workgroup's rows (60 KiB)
+
+// FULL: K is a multiple of 512 and the column groups divide it evenly: every lane of every wave has columns in every
+// pass.  Otherwise lanes past K load from the row's first columns and contribute exactly zero (their activations and
+// scale are forced to 0).
+// CGN: passes over the rows, one per group of KSW x 512 columns; a template parameter, the loop over it unrolled.
+template <bool FULL, int CGN>
+__global__ __launch_bounds__(kQuadMaxWaves * kWave) void gemv_quad_kernel(
+    const uint8_t* __restrict__ packed, const uint8_t* __restrict__ q8, const float* __restrict__ scale2,
+    const float* __restrict__ offset_p, const float* __restrict__ code2, int log2_bs, Fmt fmt, int64_t N, int64_t K,
+    const _Float16* __restrict__ x, int B, _Float16* __restrict__ y, int KSW, int RS, int rows_per_wg) {
+    // one LDS object, so that the split table sits at address 0:
+    // table | 16 levels | code2 | token sums per row and slot | block scales of the workgroup's rows
+    constexpr int kOffLut = kPairTableBytes, kOffCode2 = kOffLut + 64, kOffRed = kOffCode2 + 1024;
+    constexpr int kOffScales = kOffRed + kQuadRedBytes;
+    __shared__ __attribute__((aligned(16))) uint8_t smem[kOffScales + kQuadScaleFloats * 4];
+    static_assert(sizeof(smem) <= 160 * 1024, "LDS of one compute unit");
+    float* lut = (float*)(smem + kOffLut);
+    float* code2_lds = (float*)(smem + kOffCode2);
+    f32x4* red = (f32x4*)(smem + kOffRed);
+    float* scales = (float*)(smem + kOffScales);
+
+    const int tid = threadIdx.x;
+    const int threads = blockDim.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int lg = fmt.log2_group;
+    const float offset = offset_p[0];
+    const uint32_t lane_off = pair_lane_offset(lane);
+    const int ksw = wave % KSW, rs = wave / KSW;
+    const int c = lane >> 2, i = lane & 3;       // block of the MFMA = 32-column piece; row of the group = token
+    const int64_t r_begin = (int64_t)blockIdx.x * rows_per_wg;
+    const int64_t r_last = r_begin + rows_per_wg < N ? r_begin + rows_per_wg : N;   // one past the last row; > r_begin
+    const int n_rows = (int)(r_last - r_begin);
+    const int n_groups = (n_rows + 3) >> 2;      // groups of four rows
+
+    // ---- tables and block scales (as in nf4_gemv_slice.hip)
+    if (tid < 16) lut[tid] = fmt.codebook ? fmt.codebook[tid] : __uint_as_float(level_literal(tid));
+    for (int t = tid; t < 256; t += threads) code2_lds[t] = code2[t];
+    __syncthreads();
+    fill_split_table((float2_t*)smem, lut, tid, threads);
+    const int blocks_per_row = (int)(K >> log2_bs);
+    {
+        const int64_t b_begin = (r_begin * K) >> log2_bs;          // K is a multiple of the block size
+        const int nblk = n_rows * blocks_per_row;
+        const uint8_t* q8w = q8 + b_begin;
+        const bool q8_aligned = ((uintptr_t)q8w & 3) == 0;         // wave-uniform
+        constexpr int kTurns = 4;                                  // dwords of scale codes per thread and pass
+        for (int i0 = 4 * tid; i0 < nblk; i0 += 4 * kTurns * threads) {
+            uint32_t cq[kTurns];
+            float s2a[kTurns], s2b[kTurns];
+#pragma unroll
+            for (int t = 0; t < kTurns; ++t) {
+                const int b = i0 + 4 * t * threads;
+                cq[t] = 0;
+                s2a[t] = s2b[t] = 0.0f;
+                if (b < nblk) {
+                    if (q8_aligned && b + 4 <= nblk) {
+                        cq[t] = *(const uint32_t*)(q8w + b);
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) cq[t] |= (uint32_t)q8w[b + j < nblk ? b + j : nblk - 1] << (8 * j);
+                    }
+                    // (four or more blocks per second-level scale -- gemv_quad_eligible -- so that four consecutive
+                    // blocks touch at most two groups)
+                    s2a[t] = scale2[(b_begin + b) >> lg];
+                    s2b[t] = scale2[(b_begin + (b + 3 < nblk ? b + 3 : nblk - 1)) >> lg];
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < kTurns; ++t) {
+                const int b = i0 + 4 * t * threads;
+                if (b >= nblk) continue;
+                const int64_t g_first = (b_begin + b) >> lg;
+                f32x4 v;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float s2 = ((b_begin + b + j) >> lg) == g_first ? s2a[t] : s2b[t];
+                    const float prod = code2_lds[(cq[t] >> (8 * j)) & 0xffu] * s2;   // rounded product, then rounded sum
+                    v[j] = prod + offset;
+                }
+                if (b + 4 <= nblk) {
+                    *(f32x4*)&scales[b] = v;
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (b + j < nblk) scales[b + j] = v[j];
+                }
+            }
+        }
+    }
+    __syncthreads();                                               // tables and scales are complete
+
+    const int slots = 4 * KSW;                                     // per row: column wave x 16 lanes
+    const int my_slot = 4 * ksw + (lane >> 4);
+    const int stride = RS;                                         // in groups of four rows
+
+#pragma unroll
+    for (int cg = 0; cg < CGN; ++cg) {
+        const int64_t col0 = ((int64_t)cg * KSW + ksw) * kQuadCols;   // the wave's columns in this pass
+        const bool live = FULL || col0 + 32 * c < K;               // K is a multiple of 64: 32 columns all in or all out
+        const uint32_t le = live ? 32u * (uint32_t)c : 0u;
+        const int64_t colw = live ? col0 : 0;                      // (a wave wholly past K reads the rows' first columns)
+
+        // The lane's activations for this pass: token i, columns colw + le .. + 31.  One MFMA handles one byte of
+        // codes, i.e. two columns: its B operand is what the lookup returns -- (hi, hi) of the two weights, then
+        // (lo, lo) -- and its A operand the two activations twice, (x_even, x_odd, x_even, x_odd), so that the four
+        // products of the step are hi * x + lo * x of both columns.  16 such operands, 2 registers each.
+        u32x2 xa[16];
+        {
+            const u32x4* xb = (const u32x4*)(x + (int64_t)(i < B ? i : 0) * K + colw + le);
+            const bool on = live && i < B;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const u32x4 h = xb[v];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t pair = on ? h[j] : 0u;
+                    xa[4 * v + j] = (u32x2){pair, pair};
+                }
+            }
+        }
+        const int my_block = (int)((colw + le) >> log2_bs);        // the lane's block inside a row
+
+        // Codes of one group of four rows: one load per lane, never predicated; rows past the workgroup's last are
+        // replaced by that last row and their results dropped.  A wave-uniform pointer plus a 32-bit lane offset
+        // (rows per workgroup x K / 2 stays far below 2^31).
+        const uint8_t* rows0 = packed + ((r_begin * K) >> 1);
+        const uint32_t col_bytes = (uint32_t)((colw + le) >> 1), row_bytes = (uint32_t)(K >> 1);
+        auto load_codes = [&](int g) {
+            const int row = 4 * g + i;
+            const uint32_t rc = (uint32_t)(row < n_rows ? row : n_rows - 1);
+            const uint32_t off = __umul24(rc, row_bytes) + col_bytes;      // both factors below 2^24: one full-rate multiply-add
+            return __builtin_nontemporal_load((const u32x4*)(rows0 + off));
+        };
+        u32x4 ring[kQuadRing];
+#pragma unroll
+        for (int r = 0; r < kQuadRing; ++r) ring[r] = load_codes(rs + r * stride);
+
+        for (int g = rs; g < n_groups; g += kQuadRing * stride) {
+#pragma unroll
+            for (int r = 0; r < kQuadRing; ++r) {
+                const int gg = g + r * stride;                     // this group (may be past the end: dropped below)
+                const int row = 4 * gg + i;
+                const int rc = row < n_rows ? row : n_rows - 1;
+                float sc = scales[__umul24((uint32_t)rc, (uint32_t)blocks_per_row) + (uint32_t)my_block];
+                if constexpr (!FULL) sc = live ? sc : 0.0f;
+                // 16 lookups, two dwords of codes (four steps) ahead of the MFMAs
+                float2_t lv[2][8];
+                auto issue = [&](int h, float2_t (&dst)[8]) {
+#pragma unroll
+                    for (int d = 0; d < 2; ++d)
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) {
+                            const uint32_t a = __builtin_amdgcn_perm(ring[r][2 * h + d], lane_off, 0x0c0c0000u | ((4u + k) << 8));
+                            dst[4 * d + k] = *(const float2_t*)(smem + a);
+                        }
+                };
+                f32x4 acc0 = {0.0f, 0.0f, 0.0f, 0.0f}, acc1 = {0.0f, 0.0f, 0.0f, 0.0f};   // two chains: MFMA latency
+                issue(0, lv[0]);
+                issue(1, lv[1]);
+                lds_wait<8>();
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    if (h == 1) lds_wait<0>();
+#pragma unroll
+                    for (int b = 0; b < 8; b += 2) {               // byte 8 h + b of the lane's 16: columns 16 h + 2 b, + 1
+                        const half4_t w0 = __builtin_bit_cast(half4_t, lv[h][b]), w1 = __builtin_bit_cast(half4_t, lv[h][b + 1]);
+                        acc0 = __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(half4_t, xa[8 * h + b]), w0, acc0, 0, 0, 0);
+                        acc1 = __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(half4_t, xa[8 * h + b + 1]), w1, acc1, 0, 0, 0);
+                    }
+                }
+                const f32x4 acc = acc0 + acc1;
+                ring[r] = load_codes(gg + kQuadRing * stride);
+                // acc[m] = token m, this lane's row, this lane's 32 columns: scale, then add the 4 pieces of a DPP row
+                f32x4 v;
+#pragma unroll
+                for (int m = 0; m < 4; ++m) {
+                    float t = sc * acc[m];
+                    t = dpp_add<0x114, 0xF>(t);                    // row_shr:4
+                    t = dpp_add<0x118, 0xF>(t);                    // row_shr:8 -> lanes 12..15 hold the sums for rows 0..3
+                    v[m] = t;
+                }
+                if ((lane & 12) == 12 && row < n_rows) {
+                    f32x4* slot = red + my_slot * rows_per_wg + row;   // the four rows of a group side by side: no bank conflict
+                    if (cg == 0) *slot = v;
+                    else *slot = *slot + v;
+                }
+            }
+        }
+    }
+
+    __syncthreads();
+    // y[b][r] = the sums of row r's slots, in slot order
+    for (int o = tid; o < n_rows * B; o += threads) {
+        const int r = o / B, b = o % B;
+        const f32x4* pr = red + r;
+        float sum = 0.0f;
+        for (int s = 0; s < slots; ++s) sum += pr[s * rows_per_wg][b];
+        y[(int64_t)b * N + r_begin + r] = (_Float16)sum;
+    }
+}
+
+// Shapes it takes: up to four tokens; K from 4096 up; second-level groups of at least four blocks (the scale decoder).
+// The split of a shape: rows per workgroup, column waves, passes, row streams.
+struct QuadPlan {
+    int64_t rows;
+    int ksw, cgn, rs;
+};
+static bool plan_quad(int64_t N, int64_t K, int log2_bs, QuadPlan& p) {
+    const int nsl = (int)((K + kQuadCols - 1) / kQuadCols);        // 512-column slices of a row
+    const int64_t G = compute_units();
+    int64_t rows = (N + G - 1) / G;
+    rows = (rows + 3) / 4 * 4;
+    const int64_t cap_scales = kQuadScaleFloats / (K >> log2_bs) / 4 * 4;   // rows whose block scales fit LDS
+    if (cap_scales < 4) return false;
+    if (rows > cap_scales) rows = cap_scales;
+    // column waves: as many as keep rows x 4 KSW slots of 16 bytes inside the reduction buffer, at most 16 and nsl
+    int ksw = (int)(kQuadRedBytes / 16 / 4 / rows);
+    if (ksw > kQuadMaxWaves) ksw = kQuadMaxWaves;
+    if (ksw > nsl) ksw = nsl;
+    if (ksw < 1) return false;
+    const int cgn = (nsl + ksw - 1) / ksw;
+    if (cgn > 4) return false;
+    ksw = (nsl + cgn - 1) / cgn;                                   // even the passes out
+    int rs = kQuadMaxWaves / ksw;
+    if (rs > (int)(rows / 4)) rs = (int)(rows / 4);
+    p = {rows, ksw, cgn, rs};
+    return true;
+}
+
+// Shapes it takes: up to four tokens; rows of 4096 columns and more that four passes of a workgroup cover; second-level
+// groups of at least four blocks (the scale decoder).
+bool gemv_quad_eligible(int64_t N, int64_t K, int B, int log2_bs, const Fmt& fmt) {
+    QuadPlan p;
+    return B >= 1 && B <= 4 && N >= 1 && K >= 4096 && fmt.log2_group >= 2 && plan_quad(N, K, log2_bs, p);
+}
+
+int launch_gemv_quad(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
+                     const float* code2, int log2_bs, Fmt fmt, int64_t N, int64_t K, const _Float16* x, int B,
+                     _Float16* y, hipStream_t s) {
+    QuadPlan p;
+    if (!plan_quad(N, K, log2_bs, p)) return NF4_ERR_SHAPE;       // gemv_quad_eligible keeps such shapes away
+    const int64_t rows = p.rows;
+    const int ksw = p.ksw, cgn = p.cgn, rs = p.rs;
+    const int nsl = (int)((K + kQuadCols - 1) / kQuadCols);
+    const unsigned grid = (unsigned)((N + rows - 1) / rows);
+    const bool full = K % kQuadCols == 0 && nsl == cgn * ksw;
+#define NF4_QUAD_LAUNCH(FULL_, CGN_)                                                                             \
+    hipLaunchKernelGGL((gemv_quad_kernel<FULL_, CGN_>), dim3(grid), dim3(ksw * rs * kWave), 0, s, packed, q8, scale2, \
+                       offset, code2, log2_bs, fmt, N, K, x, B, y, ksw, rs, (int)rows)
+    switch (cgn) {
+        case 1: if (full) NF4_QUAD_LAUNCH(true, 1); else NF4_QUAD_LAUNCH(false, 1); break;
+        case 2: if (full) NF4_QUAD_LAUNCH(true, 2); else NF4_QUAD_LAUNCH(false, 2); break;
+        case 3: if (full) NF4_QUAD_LAUNCH(true, 3); else NF4_QUAD_LAUNCH(false, 3); break;
+        default: if (full) NF4_QUAD_LAUNCH(true, 4); else NF4_QUAD_LAUNCH(false, 4); break;
+    }
+#undef NF4_QUAD_LAUNCH
+    return record_hip(hipGetLastError());
+}
+
+}  // namespace nf4

@@ -70,6 +70,12 @@ int launch_gemv_slice(const uint8_t* packed, const uint8_t* q8, const float* sca
                       const float* code2, int log2_bs, Fmt fmt, int64_t N, int64_t K, const _Float16* x, int B,
                       _Float16* y, hipStream_t s);
 
+// Up to four tokens by column pieces on the 4 x 4 x 4 matrix-core instruction (nf4_gemv_quad.hip).
+bool gemv_quad_eligible(int64_t N, int64_t K, int B, int log2_bs, const Fmt& fmt);
+int launch_gemv_quad(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
+                     const float* code2, int log2_bs, Fmt fmt, int64_t N, int64_t K, const _Float16* x, int B,
+                     _Float16* y, hipStream_t s);
+
 // nf4_dequant_gemv_ws after its argument checks: FMA kernels for one and two tokens, split-K on the matrix cores
 // with `partial` (plan_split(N, K, B).splits * B * N floats, written before they are read) above that.
 int launch_gemv_ws(const uint8_t* packed, const uint8_t* q8, const float* scale2, const float* offset,
