@@ -74,10 +74,16 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
     constexpr int kThreads = W * kWave;
     constexpr int kTokens = 16 * TG;
     constexpr int kH = WIN / 128;                // 128-bit pieces of codes per lane and row: k = 128 h + 32 g ..
-    constexpr int kXRowBytes = 2 * WIN + 16;     // token row of the activation tile: an odd number of 16-byte units
+    // Token row of the activation tile.  The 128-bit reads of the MFMA B operands, lane (token, g) at token * row +
+    // 16 g (SPLIT) or + 64 g, were timed on MI355X for rows of 2 WIN + 16, + 32, + 48 and + 64 bytes: the first
+    // form runs at the LDS's full rate (4.2 cycles per wave instruction) only with + 32, at half of it otherwise.
+    constexpr int kXRowBytes = 2 * WIN + (SPLIT ? 32 : 16);
     constexpr int kPiecesPerToken = WIN / 8;     // 16-byte pieces of one token's window
     constexpr int kChunks = kTokens * kPiecesPerToken;
-    constexpr int kTurnRow = 80;                 // bytes per row in the transpose buffer (64 + 16: conflict-free)
+    // Transpose buffer: 64 bytes per row, the four 16-byte pieces of row r at positions piece ^ (r / 4).  Written by
+    // lane (row l / 4, piece l % 4) that is the wave's 1 KiB in order, 16 lanes per 256 bytes: full rate (rows of 80
+    // bytes took three times as long); read by lane (row l % 16, group l / 16).
+    constexpr int kTurnRow = 64;
     constexpr int kU = (kChunks + kThreads - 1) / kThreads;
     constexpr int kXTileBytes = kTokens * kXRowBytes;
     constexpr int kTurnBytes = 16 * kTurnRow;    // one 16-byte piece of each of 16 rows
@@ -257,15 +263,17 @@ __global__ __launch_bounds__(W * kWave) void gemm_splitk_kernel(const uint8_t* _
 #pragma unroll
         for (int h = 0; h < kH; ++h) {
 #pragma unroll
-            for (int r = 0; r < RG; ++r) *(u32x4*)(turn + r * kTurnBytes + lrow * kTurnRow + 16 * lpc) = cr.c[r][h];
+            for (int r = 0; r < RG; ++r)
+                *(u32x4*)(turn + r * kTurnBytes + lrow * kTurnRow + 16 * (lpc ^ (lrow >> 2))) = cr.c[r][h];
             wave_lds_fence();
 #pragma unroll
             for (int r = 0; r < RG; ++r) {
                 if constexpr (SPLIT) {           // dword g of each of the four pieces: an MFMA step stays in one block
                     const uint32_t* tp = (const uint32_t*)(turn + r * kTurnBytes + sub * kTurnRow + 4 * g);
-                    c[r][h] = (u32x4){tp[0], tp[4], tp[8], tp[12]};
+                    const int sw = sub >> 2;
+                    c[r][h] = (u32x4){tp[4 * sw], tp[4 * (1 ^ sw)], tp[4 * (2 ^ sw)], tp[4 * (3 ^ sw)]};
                 } else {
-                    c[r][h] = *(const u32x4*)(turn + r * kTurnBytes + sub * kTurnRow + 16 * g);
+                    c[r][h] = *(const u32x4*)(turn + r * kTurnBytes + sub * kTurnRow + 16 * (g ^ (sub >> 2)));
                 }
             }
             wave_lds_fence();                    // read before the next h overwrites the buffer

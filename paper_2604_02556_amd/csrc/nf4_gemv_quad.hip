@@ -132,20 +132,66 @@ __global__ __launch_bounds__(kQuadMaxWaves * kWave) void gemv_quad_kernel(
     const int my_slot = 4 * ksw + (lane >> 4);
     const int stride = RS;                                         // in groups of four rows
 
+    // The wave's columns in pass cg: lane piece c of column wave cg * KSW + ksw.  A lane past K reads the rows' first
+    // columns instead (and contributes zero).
+    auto pass_columns = [&](int cg, bool& live, int64_t& first) {
+        const int64_t col0 = ((int64_t)cg * KSW + ksw) * kQuadCols;
+        live = FULL || col0 + 32 * c < K;                          // K is a multiple of 64: 32 columns all in or all out
+        first = live ? col0 + 32 * c : 0;                          // the lane's first column
+    };
+    // Codes of one group of four rows: one load per lane, never predicated; rows past the workgroup's last are
+    // replaced by that last row and their results dropped.  A wave-uniform pointer plus a 32-bit lane offset
+    // (rows per workgroup x K / 2 stays far below 2^31).
+    const uint8_t* rows0 = packed + ((r_begin * K) >> 1);
+    const uint32_t row_bytes = (uint32_t)(K >> 1);
+    uint32_t col_bytes[CGN];
 #pragma unroll
     for (int cg = 0; cg < CGN; ++cg) {
-        const int64_t col0 = ((int64_t)cg * KSW + ksw) * kQuadCols;   // the wave's columns in this pass
-        const bool live = FULL || col0 + 32 * c < K;               // K is a multiple of 64: 32 columns all in or all out
-        const uint32_t le = live ? 32u * (uint32_t)c : 0u;
-        const int64_t colw = live ? col0 : 0;                      // (a wave wholly past K reads the rows' first columns)
+        bool live;
+        int64_t first;
+        pass_columns(cg, live, first);
+        col_bytes[cg] = (uint32_t)(first >> 1);
+    }
+    auto load_codes = [&](int g, uint32_t cb) {
+        const int row = 4 * g + i;
+        const uint32_t rc = (uint32_t)(row < n_rows ? row : n_rows - 1);
+        const uint32_t off = __umul24(rc, row_bytes) + cb;         // both factors below 2^24: one full-rate multiply-add
+        return __builtin_nontemporal_load((const u32x4*)(rows0 + off));
+    };
+    // Four groups in flight per wave, and the ring does not drain between passes: in the last round of a pass the
+    // reloads fetch the first groups of the next pass (with 8 to 28 groups per wave and pass, stopping and
+    // restarting the stream at every pass cost 2 to 3 us each).
+    u32x4 ring[kQuadRing];
+#pragma unroll
+    for (int r = 0; r < kQuadRing; ++r) ring[r] = load_codes(rs + r * stride, col_bytes[0]);
 
-        // The lane's activations for this pass: token i, columns colw + le .. + 31.  One MFMA handles one byte of
+    // The 16 lookups of a group in two halves (two dwords of codes, eight lookups, four MFMA steps each), one half
+    // ahead of the MFMAs: while the matrix core works on one half the LDS serves the other -- across groups and
+    // passes too, the first half of the next group is requested before the second half of this one is multiplied.
+    float2_t lva[8], lvb[8];
+    auto issue = [&](const u32x4& codes, int h, float2_t (&dst)[8]) {
+#pragma unroll
+        for (int d = 0; d < 2; ++d)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const uint32_t a = __builtin_amdgcn_perm(codes[2 * h + d], lane_off, 0x0c0c0000u | ((4u + k) << 8));
+                dst[4 * d + k] = *(const float2_t*)(smem + a);
+            }
+    };
+    issue(ring[0], 0, lva);
+
+#pragma unroll
+    for (int cg = 0; cg < CGN; ++cg) {
+        bool live;
+        int64_t first;
+        pass_columns(cg, live, first);
+        // The lane's activations for this pass: token i, columns first .. first + 31.  One MFMA handles one byte of
         // codes, i.e. two columns: its B operand is what the lookup returns -- (hi, hi) of the two weights, then
         // (lo, lo) -- and its A operand the two activations twice, (x_even, x_odd, x_even, x_odd), so that the four
         // products of the step are hi * x + lo * x of both columns.  16 such operands, 2 registers each.
         u32x2 xa[16];
         {
-            const u32x4* xb = (const u32x4*)(x + (int64_t)(i < B ? i : 0) * K + colw + le);
+            const u32x4* xb = (const u32x4*)(x + (int64_t)(i < B ? i : 0) * K + first);
             const bool on = live && i < B;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
@@ -157,24 +203,17 @@ __global__ __launch_bounds__(kQuadMaxWaves * kWave) void gemv_quad_kernel(
                 }
             }
         }
-        const int my_block = (int)((colw + le) >> log2_bs);        // the lane's block inside a row
-
-        // Codes of one group of four rows: one load per lane, never predicated; rows past the workgroup's last are
-        // replaced by that last row and their results dropped.  A wave-uniform pointer plus a 32-bit lane offset
-        // (rows per workgroup x K / 2 stays far below 2^31).
-        const uint8_t* rows0 = packed + ((r_begin * K) >> 1);
-        const uint32_t col_bytes = (uint32_t)((colw + le) >> 1), row_bytes = (uint32_t)(K >> 1);
-        auto load_codes = [&](int g) {
-            const int row = 4 * g + i;
-            const uint32_t rc = (uint32_t)(row < n_rows ? row : n_rows - 1);
-            const uint32_t off = __umul24(rc, row_bytes) + col_bytes;      // both factors below 2^24: one full-rate multiply-add
-            return __builtin_nontemporal_load((const u32x4*)(rows0 + off));
-        };
-        u32x4 ring[kQuadRing];
+        const int my_block = (int)(first >> log2_bs);              // the lane's block inside a row
+        auto multiply = [&](const float2_t (&lv)[8], int h, f32x4& acc0, f32x4& acc1) {
 #pragma unroll
-        for (int r = 0; r < kQuadRing; ++r) ring[r] = load_codes(rs + r * stride);
-
+            for (int b = 0; b < 8; b += 2) {                       // byte 8 h + b of the lane's 16: columns 16 h + 2 b, + 1
+                const half4_t w0 = __builtin_bit_cast(half4_t, lv[b]), w1 = __builtin_bit_cast(half4_t, lv[b + 1]);
+                acc0 = __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(half4_t, xa[8 * h + b]), w0, acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(half4_t, xa[8 * h + b + 1]), w1, acc1, 0, 0, 0);
+            }
+        };
         for (int g = rs; g < n_groups; g += kQuadRing * stride) {
+            const bool last_round = g + kQuadRing * stride >= n_groups;   // wave-uniform
 #pragma unroll
             for (int r = 0; r < kQuadRing; ++r) {
                 const int gg = g + r * stride;                     // this group (may be past the end: dropped below)
@@ -182,42 +221,34 @@ __global__ __launch_bounds__(kQuadMaxWaves * kWave) void gemv_quad_kernel(
                 const int rc = row < n_rows ? row : n_rows - 1;
                 float sc = scales[__umul24((uint32_t)rc, (uint32_t)blocks_per_row) + (uint32_t)my_block];
                 if constexpr (!FULL) sc = live ? sc : 0.0f;
-                // 16 lookups, two dwords of codes (four steps) ahead of the MFMAs
-                float2_t lv[2][8];
-                auto issue = [&](int h, float2_t (&dst)[8]) {
-#pragma unroll
-                    for (int d = 0; d < 2; ++d)
-#pragma unroll
-                        for (int k = 0; k < 4; ++k) {
-                            const uint32_t a = __builtin_amdgcn_perm(ring[r][2 * h + d], lane_off, 0x0c0c0000u | ((4u + k) << 8));
-                            dst[4 * d + k] = *(const float2_t*)(smem + a);
-                        }
-                };
+                issue(ring[r], 1, lvb);
+                // its codes are all turned into addresses: the slot's next group, in this pass or the next one
+                if (cg + 1 < CGN)
+                    ring[r] = load_codes(last_round ? rs + r * stride : gg + kQuadRing * stride,
+                                         last_round ? col_bytes[cg + 1] : col_bytes[cg]);
+                else
+                    ring[r] = load_codes(gg + kQuadRing * stride, col_bytes[cg]);
                 f32x4 acc0 = {0.0f, 0.0f, 0.0f, 0.0f}, acc1 = {0.0f, 0.0f, 0.0f, 0.0f};   // two chains: MFMA latency
-                issue(0, lv[0]);
-                issue(1, lv[1]);
                 lds_wait<8>();
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    if (h == 1) lds_wait<0>();
-#pragma unroll
-                    for (int b = 0; b < 8; b += 2) {               // byte 8 h + b of the lane's 16: columns 16 h + 2 b, + 1
-                        const half4_t w0 = __builtin_bit_cast(half4_t, lv[h][b]), w1 = __builtin_bit_cast(half4_t, lv[h][b + 1]);
-                        acc0 = __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(half4_t, xa[8 * h + b]), w0, acc0, 0, 0, 0);
-                        acc1 = __builtin_amdgcn_mfma_f32_4x4x4f16(__builtin_bit_cast(half4_t, xa[8 * h + b + 1]), w1, acc1, 0, 0, 0);
-                    }
-                }
+                multiply(lva, 0, acc0, acc1);
+                issue(ring[(r + 1) % kQuadRing], 0, lva);          // the next group's first half (after the last group: unused)
+                lds_wait<8>();
+                multiply(lvb, 1, acc0, acc1);
                 const f32x4 acc = acc0 + acc1;
-                ring[r] = load_codes(gg + kQuadRing * stride);
                 // acc[m] = token m, this lane's row, this lane's 32 columns: scale, then add the 4 pieces of a DPP row
+                // (the four tokens step by step: a lane shift must wait two instructions for its operand)
                 f32x4 v;
 #pragma unroll
-                for (int m = 0; m < 4; ++m) {
-                    float t = sc * acc[m];
-                    t = dpp_add<0x114, 0xF>(t);                    // row_shr:4
-                    t = dpp_add<0x118, 0xF>(t);                    // row_shr:8 -> lanes 12..15 hold the sums for rows 0..3
-                    v[m] = t;
-                }
+                for (int m = 0; m < 4; ++m) v[m] = sc * acc[m];
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int m = 0; m < 4; ++m) v[m] = dpp_add<0x114, 0xF>(v[m]);      // row_shr:4
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int m = 0; m < 4; ++m) v[m] = dpp_add<0x118, 0xF>(v[m]);      // row_shr:8 -> lanes 12..15 hold the sums for rows 0..3
+                // (used here, before the branch: otherwise the compiler moves the last adds into the branch, where
+                // they cannot merge with the lane shifts, and pays a move, the add and a cleared register instead)
+                asm volatile("" : "+v"(v));
                 if ((lane & 12) == 12 && row < n_rows) {
                     f32x4* slot = red + my_slot * rows_per_wg + row;   // the four rows of a group side by side: no bank conflict
                     if (cg == 0) *slot = v;
@@ -226,6 +257,7 @@ __global__ __launch_bounds__(kQuadMaxWaves * kWave) void gemv_quad_kernel(
             }
         }
     }
+    lds_wait<0>();                                                 // the lookups requested last are not used
 
     __syncthreads();
     // y[b][r] = the sums of row r's slots, in slot order
