@@ -10,8 +10,10 @@
 // (16 TG tokens x 2 WIN bytes) in LDS serves them all: the workgroup loads it
 // once, coalesced, one window ahead, into the other half of a double buffer, and
 // the waves read their MFMA B operands from it with ds_read_b128.  Token rows are
-// 2 WIN + 16 bytes apart, so the 16 lanes that the LDS serves together fall into
-// 8 distinct groups of 4 banks (conflict-free at the rate of a 128-bit read).
+// 2 WIN + 32 (SPLIT) or + 16 bytes apart: timed on MI355X, the SPLIT form's reads
+// (lane (token, g) at 16 g inside the row) run at the LDS's full rate with + 32
+// only (4.2 cycles per wave instruction, 8.0 with + 16, + 48, + 64); the other
+// form's (64 g inside the row) take 8.0 whatever the padding.
 //
 // Because x comes from LDS, a lane is free to take whichever k it likes: lane
 // (row, group g) expands k = 128 h + 32 g .. + 31 of the window as its piece h,
