@@ -467,6 +467,15 @@ def leg_quantize(torch, nf4, synth, stream, gen, src):
         t = time_on_stream(torch, stream, lambda: nf4.nf4_quantize(w, n, bs, bb["packed"], bb["absmax"], stream=stream), 10)
         by = n * (4.0 + 0.5 + 4.0 / bs)
         res["other_block_sizes"][str(bs)] = {"us": round(t, 2), "GB/s": round(by / (t * 1e-6) / 1e9, 1)}
+    # another 16-level table (FP4-style E2M1 in sign-magnitude order, read from memory): thresholds found on the device
+    table = torch.from_numpy(synth.e2m1_codebook()).to(src.device)
+    ws = torch.empty(nf4.QUANTIZE_CODEBOOK_WORKSPACE_BYTES, dtype=torch.uint8, device=src.device)
+    t = time_on_stream(torch, stream, lambda: nf4.nf4_quantize_codebook(w, n, 64, table, b["packed"], b["absmax"], ws,
+                                                                         stream=stream), 10)
+    t_ref = time_on_stream(torch, stream, lambda: nf4.nf4_quantize_ref_codebook(w, n, 64, table, 256, b["packed"],
+                                                                                 b["absmax"], stream=stream), 3)
+    res["e2m1_codebook"] = {"us": round(t, 2), "GB/s": round(bytes_ / (t * 1e-6) / 1e9, 1),
+                            "reference_quantizer_us": round(t_ref, 2)}
     return res
 
 

@@ -290,6 +290,29 @@ int nf4_quantize(const float* src, int64_t n, int blocksize, uint8_t* packed, fl
                  void* stream);
 
 /*
+ * nf4_quantize for any 16 levels (Sec. V-A: the data type as a parameter):
+ * writes exactly the packed[] and absmax[] that nf4_quantize_ref_codebook
+ * writes for `codebook` (float[16], device; NULL = NF4, then nf4_quantize), bit
+ * for bit.  The decision thresholds of the levels are found on the device by
+ * a one-workgroup kernel ahead of the quantiser, into `workspace` (device,
+ * 8-byte aligned, at least NF4_QUANTIZE_CODEBOOK_WORKSPACE_BYTES, else
+ * NF4_ERR_SIZE; owned by the caller, contents undefined before and after;
+ * calls that share it must not overlap).  The levels may be in any order and
+ * repeat (FP4-style tables in sign-magnitude order with +0 and -0).  Tables
+ * whose levels are finite, whose distinct values are at least 2^-10 and 2^-12
+ * of their magnitude apart, and of whose decision thresholds none lies within
+ * 2^-30 of zero and no two fall into one interval of 1/32 (NF4, E2M1, evenly
+ * spaced levels, any sensible 4-bit type) run at the speed
+ * of nf4_quantize; any other table is quantised by the
+ * reference kernel inside the same call, with the same results.  The call
+ * never waits for the GPU.
+ */
+#define NF4_QUANTIZE_CODEBOOK_WORKSPACE_BYTES ((size_t)1024)
+int nf4_quantize_codebook(const float* src, int64_t n, int blocksize, const float* codebook,
+                          uint8_t* packed, float* absmax, void* workspace, size_t workspace_bytes,
+                          void* stream);
+
+/*
  * The second level alone: double-quantises an existing array of nb block scales
  * (e.g. nf4_quantize's absmax) exactly as nf4_quantize_ref_codebook does, bit for
  * bit: code2[u] = (u - 127)/127, offset = mean(absmax) (the double-precision sum

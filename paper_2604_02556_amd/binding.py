@@ -68,6 +68,8 @@ def lib():
     for f in (L.nf4_dequantize_codebook, L.nf4_dequantize_dq_codebook, L.nf4_quantize_ref_codebook):
         f.restype = i32
     L.nf4_quantize.argtypes = [vp, i64, i32, vp, vp, vp]
+    L.nf4_quantize_codebook.argtypes = [vp, i64, i32, vp, vp, vp, vp, c.c_size_t, vp]
+    L.nf4_quantize_codebook.restype = i32
     L.nf4_dq_encode.argtypes = [vp, i64, i32, vp, vp, vp, vp, vp]
     for f in (L.nf4_dequantize, L.nf4_dequantize_dq, L.nf4_dequant_gemv, L.nf4_quantize_ref, L.nf4_quantize,
               L.nf4_last_hip_error):
@@ -233,6 +235,15 @@ def nf4_dq_encode(absmax, nb, dq_group, absmax_q8, scale2, offset, code2, stream
 
 def nf4_quantize(src, n, blocksize, packed, absmax, stream=None):
     _check(lib().nf4_quantize(_ptr(src), n, blocksize, _ptr(packed), _ptr(absmax), _stream(stream)))
+
+
+QUANTIZE_CODEBOOK_WORKSPACE_BYTES = 1024         # NF4_QUANTIZE_CODEBOOK_WORKSPACE_BYTES of include/nf4.h
+
+
+def nf4_quantize_codebook(src, n, blocksize, codebook, packed, absmax, workspace, stream=None):
+    _check(lib().nf4_quantize_codebook(_ptr(src), n, blocksize, _ptr(codebook), _ptr(packed), _ptr(absmax),
+                                       _ptr(workspace), 0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                       _stream(stream)))
 
 
 # ---- allocation helpers (plumbing only: sizes of the format's arrays) ----

@@ -106,6 +106,115 @@ static const QuantBins* quant_bins() {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+// The bins of a caller's codebook, built on the device (the levels live in device memory and the call must not wait
+// for the GPU): what build_bins does on the host, by the same bisection with the same FP32 predicate, one threshold
+// per lane -- for levels in any order, with repeats (FP4-style tables are in sign-magnitude order and hold +0 and -0):
+//   * the distinct values are ranked; a value's code is the lowest index that holds it (the 16-way search keeps the
+//     first of equal distances);
+//   * between neighbouring values u < u' the search moves to u' where u' is strictly nearer -- or just as near, when
+//     the code of u' is the lower of the two --, a predicate that is monotone in x: one threshold per pair;
+//   * a bin stores the threshold inside it and the codes on both sides of it (below: the code of the number of
+//     thresholds under the bin), so a level index costs the same two table reads as for NF4.
+// `usable` = 0 sends the call to the reference kernel: a level that is not finite, neighbouring values closer than
+// 2^-10 or than 2^-12 of their magnitude (rounded distances must order like exact ones), a threshold within 2^-30
+// of zero (where the tuned kernel's division is not the IEEE one), or two thresholds in one bin of 1/32.
+struct DeviceBins {
+    QuantBins bins;          // base[b] = code below the bin's threshold | code at and above it << 16
+    int usable;
+};
+
+__global__ __launch_bounds__(128) void quant_bins_kernel(const float* __restrict__ codebook, DeviceBins* __restrict__ out) {
+    __shared__ float level[16];
+    __shared__ float uval[16];       // distinct values, ascending
+    __shared__ int ucode[17];        // their codes (one more: read, never used, beside the last threshold)
+    __shared__ float theta[15];
+    __shared__ int bin[15];
+    __shared__ int bad, count;
+    const int tid = threadIdx.x;
+    if (tid < 16) level[tid] = codebook[tid];
+    if (tid == 0) bad = 0;
+    if (tid < 17) ucode[tid] = 0;
+    __syncthreads();
+    if (tid < 16) {
+        const float v = level[tid];
+        if (!(__builtin_fabsf(v) < __builtin_inff())) bad = 1;     // (any writer writes the same value)
+        bool first = true;           // no lower index holds the same value
+        int rank = 0;                // distinct values below v
+        for (int j = 0; j < 16; ++j) {
+            bool first_j = true;
+            for (int i = 0; i < j; ++i) first_j = first_j && !(level[i] == level[j]);
+            if (j < tid && level[j] == v) first = false;
+            if (first_j && level[j] < v) ++rank;
+        }
+        if (first) {
+            uval[rank] = v;
+            ucode[rank] = tid;
+        }
+        if (tid == 0) {
+            int m = 0;
+            for (int j = 0; j < 16; ++j) {
+                bool first_j = true;
+                for (int i = 0; i < j; ++i) first_j = first_j && !(level[i] == level[j]);
+                m += first_j ? 1 : 0;
+            }
+            count = m;
+        }
+    }
+    __syncthreads();
+    if (tid < 15) {
+        theta[tid] = __builtin_inff();
+        bin[tid] = kBins;                                          // in no bin, below none
+        if (bad == 0 && tid + 1 < count) {
+            const float lo_level = uval[tid], hi_level = uval[tid + 1];
+            const float gap = hi_level - lo_level;
+            const float mag = __builtin_fmaxf(__builtin_fabsf(lo_level), __builtin_fabsf(hi_level));
+            if (!(gap >= 0x1p-10f) || !(gap >= 0x1p-12f * mag)) {
+                bad = 1;
+            } else {
+                const bool ties_go_up = ucode[tid + 1] < ucode[tid];
+                // monotone map between FP32 values and integers; the predicate is false at lo, true at hi
+                auto key_of = [](float f) {
+                    const uint32_t u = __float_as_uint(f);
+                    return (u >> 31) ? -(int64_t)(u & 0x7fffffffu) : (int64_t)u;
+                };
+                auto float_of = [](int64_t k) { return __uint_as_float(k < 0 ? (0x80000000u | (uint32_t)(-k)) : (uint32_t)k); };
+                int64_t lo = key_of(lo_level), hi = key_of(hi_level);
+                while (hi - lo > 1) {
+                    const int64_t mid = lo + (hi - lo) / 2;
+                    const float x = float_of(mid);
+                    const float d_lo = __builtin_fabsf(x - lo_level);
+                    const float d_hi = __builtin_fabsf(x - hi_level);
+                    if (ties_go_up ? d_hi <= d_lo : d_hi < d_lo) hi = mid; else lo = mid;
+                }
+                const float th = float_of(hi);
+                theta[tid] = th;
+                // (div_by_block_scale is the correctly rounded quotient only down to about 2^-38: no threshold there)
+                if (__builtin_fabsf(th) < 0x1p-30f) bad = 1;
+                if (th <= -1.0f) {
+                    bin[tid] = -1;                                 // reached by every x / absmax: below every bin
+                } else if (th <= 1.0f) {
+                    const float pos = __builtin_fmaf(th, 32.0f, 32.0f);
+                    bin[tid] = pos <= 0.0f ? 0 : (int)(uint32_t)pos;
+                }                                                  // else never reached
+            }
+        }
+    }
+    __syncthreads();
+    if (tid < kBins) {
+        int below = 0, inside = 0;
+        float th = __builtin_inff();
+        for (int k = 0; k < 15; ++k) {
+            if (bin[k] < tid) ++below;
+            if (bin[k] == tid) { th = theta[k]; ++inside; }
+        }
+        if (inside > 1) bad = 1;
+        out->bins.theta[tid] = th;
+        out->bins.base[tid] = (uint32_t)ucode[below] | ((uint32_t)ucode[below + 1] << 16);
+    }
+    __syncthreads();
+    if (tid == 0) out->usable = bad ? 0 : 1;
+}
+
 template <int CTRL>
 __device__ __forceinline__ float dpp_max(float v) {
     // every lane has a valid source for these permutations; full masks + bound_ctrl let the
@@ -146,10 +255,12 @@ __device__ __forceinline__ float max_across_rows(float a, int lane, bool all_fou
 // sizes that do not fill a tile) loads element by element with zeros past n -- which neither raise a block's
 // maximum nor, as x / absmax = 0, give anything but the zero level's code to the unused nibble of an odd n -- and
 // stores only the bytes and scales that exist.
-template <int LOG2BS>
+// MEM: the bins come from device memory (quant_bins_kernel built them from the caller's levels) instead of the kernel
+// arguments, and the kernel does nothing when that table is marked unusable (the reference kernel then does the work).
+template <int LOG2BS, bool MEM>
 __global__ __launch_bounds__((LOG2BS == 12 ? 2 : 1) * kWave) void quantize_tiles_kernel(
-    const float* __restrict__ src, QuantBins qb, int64_t n, uint8_t* __restrict__ packed,
-    float* __restrict__ absmax) {
+    const float* __restrict__ src, QuantBins qb, const DeviceBins* __restrict__ dbins, int64_t n,
+    uint8_t* __restrict__ packed, float* __restrict__ absmax) {
     constexpr int kWaves = LOG2BS == 12 ? 2 : 1;
     constexpr int kLoadsPerBlock = LOG2BS >= 11 ? 8 : (1 << (LOG2BS > 8 ? LOG2BS - 8 : 0));
     __shared__ float theta_lds[kBins];
@@ -157,11 +268,21 @@ __global__ __launch_bounds__((LOG2BS == 12 ? 2 : 1) * kWave) void quantize_tiles
     __shared__ float wave_max[2];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    theta_lds[lane] = qb.theta[lane];                    // (both waves of a 4096-block workgroup write the same values)
-    base_lds[lane] = qb.base[lane];
-    if (lane == 0) {
-        theta_lds[kBins - 1] = qb.theta[kBins - 1];
-        base_lds[kBins - 1] = qb.base[kBins - 1];
+    if constexpr (MEM) {
+        if (dbins->usable == 0) return;                  // the same for every thread of the grid
+        theta_lds[lane] = dbins->bins.theta[lane];
+        base_lds[lane] = dbins->bins.base[lane];
+        if (lane == 0) {
+            theta_lds[kBins - 1] = dbins->bins.theta[kBins - 1];
+            base_lds[kBins - 1] = dbins->bins.base[kBins - 1];
+        }
+    } else {
+        theta_lds[lane] = qb.theta[lane];                // (both waves of a 4096-block workgroup write the same values)
+        base_lds[lane] = qb.base[lane];
+        if (lane == 0) {
+            theta_lds[kBins - 1] = qb.theta[kBins - 1];
+            base_lds[kBins - 1] = qb.base[kBins - 1];
+        }
     }
     wave_lds_fence();
 
@@ -249,7 +370,13 @@ __global__ __launch_bounds__((LOG2BS == 12 ? 2 : 1) * kWave) void quantize_tiles
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const uint32_t b = (uint32_t)__builtin_fmaf(xn[e], 32.0f, 32.0f);   // 0..64; NaN -> 0
-            code[e] = base_lds[b] + (xn[e] >= theta_lds[b] ? 1u : 0u);
+            if constexpr (MEM) {
+                const uint32_t both = base_lds[b];                 // the codes below and from the bin's threshold on
+                const uint32_t c = xn[e] >= theta_lds[b] ? both >> 16 : both & 0xffffu;
+                code[e] = xn[e] == xn[e] ? c : 0u;                 // NaN: every distance is NaN, the search keeps code 0
+            } else {
+                code[e] = base_lds[b] + (xn[e] >= theta_lds[b] ? 1u : 0u);
+            }
         }
         // element 2i in the high nibble of byte i; two bytes per lane, little-endian
         const uint32_t two_bytes = (code[0] << 4) | code[1] | (code[2] << 12) | (code[3] << 8);
@@ -263,21 +390,40 @@ __global__ __launch_bounds__((LOG2BS == 12 ? 2 : 1) * kWave) void quantize_tiles
     }
 }
 
+// `dbins` = nullptr: the NF4 bins in `qb` (kernel arguments); otherwise the bins in device memory.
 template <int LOG2BS>
-static int launch_tiles(const float* src, const QuantBins& qb, int64_t n, uint8_t* packed, float* absmax,
-                        hipStream_t s) {
+static int launch_tiles(const float* src, const QuantBins& qb, const DeviceBins* dbins, int64_t n, uint8_t* packed,
+                        float* absmax, hipStream_t s) {
     constexpr int kWaves = LOG2BS == 12 ? 2 : 1;
     const int64_t per_group = (int64_t)kWaves * kQTileElems;
     const int64_t groups = (n + per_group - 1) / per_group;
     if (groups > 0x7fffffffLL) return NF4_ERR_SIZE;
-    hipLaunchKernelGGL(quantize_tiles_kernel<LOG2BS>, dim3((unsigned)groups), dim3(kWaves * kWave), 0, s, src, qb, n,
-                       packed, absmax);
+    if (dbins)
+        hipLaunchKernelGGL((quantize_tiles_kernel<LOG2BS, true>), dim3((unsigned)groups), dim3(kWaves * kWave), 0, s, src,
+                           qb, dbins, n, packed, absmax);
+    else
+        hipLaunchKernelGGL((quantize_tiles_kernel<LOG2BS, false>), dim3((unsigned)groups), dim3(kWaves * kWave), 0, s, src,
+                           qb, dbins, n, packed, absmax);
     return record_hip(hipGetLastError());
 }
 
+static int launch_tiles_any(int log2_bs, const float* src, const QuantBins& qb, const DeviceBins* dbins, int64_t n,
+                            uint8_t* packed, float* absmax, hipStream_t s) {
+    switch (log2_bs) {
+        case 6: return launch_tiles<6>(src, qb, dbins, n, packed, absmax, s);
+        case 7: return launch_tiles<7>(src, qb, dbins, n, packed, absmax, s);
+        case 8: return launch_tiles<8>(src, qb, dbins, n, packed, absmax, s);
+        case 9: return launch_tiles<9>(src, qb, dbins, n, packed, absmax, s);
+        case 10: return launch_tiles<10>(src, qb, dbins, n, packed, absmax, s);
+        case 11: return launch_tiles<11>(src, qb, dbins, n, packed, absmax, s);
+        default: return launch_tiles<12>(src, qb, dbins, n, packed, absmax, s);
+    }
+}
+
 // the reference kernel (nf4_quantize_ref.hip) finishes what does not fill a tile
-int launch_quantize_ref_range(const float* src, int64_t n, int blocksize, const float* codebook, uint8_t* packed,
-                              float* absmax, hipStream_t s);
+// (`skip_if` != nullptr: the kernel does nothing when *skip_if is not 0)
+int launch_quantize_ref_range(const float* src, int64_t n, int blocksize, const float* codebook, const int* skip_if,
+                              uint8_t* packed, float* absmax, hipStream_t s);
 
 }  // namespace nf4
 
@@ -292,14 +438,31 @@ extern "C" int nf4_quantize(const float* src, int64_t n, int blocksize, uint8_t*
     hipStream_t s = (hipStream_t)stream;
     const QuantBins* qb = quant_bins();
     const int log2_bs = log2_blocksize(blocksize);
-    if (qb == nullptr) return launch_quantize_ref_range(src, n, blocksize, nullptr, packed, absmax, s);
-    switch (log2_bs) {
-        case 6: return launch_tiles<6>(src, *qb, n, packed, absmax, s);
-        case 7: return launch_tiles<7>(src, *qb, n, packed, absmax, s);
-        case 8: return launch_tiles<8>(src, *qb, n, packed, absmax, s);
-        case 9: return launch_tiles<9>(src, *qb, n, packed, absmax, s);
-        case 10: return launch_tiles<10>(src, *qb, n, packed, absmax, s);
-        case 11: return launch_tiles<11>(src, *qb, n, packed, absmax, s);
-        default: return launch_tiles<12>(src, *qb, n, packed, absmax, s);
-    }
+    if (qb == nullptr) return launch_quantize_ref_range(src, n, blocksize, nullptr, nullptr, packed, absmax, s);
+    return launch_tiles_any(log2_bs, src, *qb, nullptr, n, packed, absmax, s);
+}
+
+extern "C" int nf4_quantize_codebook(const float* src, int64_t n, int blocksize, const float* codebook, uint8_t* packed,
+                                     float* absmax, void* workspace, size_t workspace_bytes, void* stream) {
+    using namespace nf4;
+    static_assert(sizeof(DeviceBins) <= NF4_QUANTIZE_CODEBOOK_WORKSPACE_BYTES, "workspace of nf4_quantize_codebook");
+    if (codebook == nullptr) return nf4_quantize(src, n, blocksize, packed, absmax, stream);
+    if (n < 0) return NF4_ERR_SIZE;
+    const int log2_bs = log2_blocksize(blocksize);
+    if (log2_bs < 0) return NF4_ERR_BLOCKSIZE;
+    if (n == 0) return NF4_OK;
+    if (!src || !packed || !absmax || !workspace) return NF4_ERR_NULL;
+    if (!aligned(src, 16) || !aligned(absmax, 4) || !aligned(packed, 2) || !aligned(codebook, 4) || !aligned(workspace, 8))
+        return NF4_ERR_ALIGN;
+    if (workspace_bytes < NF4_QUANTIZE_CODEBOOK_WORKSPACE_BYTES) return NF4_ERR_SIZE;
+    hipStream_t s = (hipStream_t)stream;
+    DeviceBins* dbins = (DeviceBins*)workspace;
+    hipLaunchKernelGGL(quant_bins_kernel, dim3(1), dim3(128), 0, s, codebook, dbins);
+    int rc = record_hip(hipGetLastError());
+    if (rc != NF4_OK) return rc;
+    // one of the two does the work: the tiles kernel when the table is usable, the reference kernel when it is not
+    static const QuantBins unused = {};
+    rc = launch_tiles_any(log2_bs, src, unused, dbins, n, packed, absmax, s);
+    if (rc != NF4_OK) return rc;
+    return launch_quantize_ref_range(src, n, blocksize, codebook, &dbins->usable, packed, absmax, s);
 }

@@ -41,8 +41,10 @@ __device__ __forceinline__ unsigned nearest_code(const float* lut, float xn) {
 __global__ __launch_bounds__(kQThreads) void quantize_kernel(const float* __restrict__ src, int64_t n,
                                                              int blocksize, int64_t nb,
                                                              const float* __restrict__ codebook,
+                                                             const int* __restrict__ skip_if,
                                                              uint8_t* __restrict__ packed,
                                                              float* __restrict__ absmax) {
+    if (skip_if && *skip_if != 0) return;                  // the tuned kernel has done the work (nf4_quantize_codebook)
     __shared__ float lut[16];
     if (threadIdx.x < 16) lut[threadIdx.x] = codebook ? codebook[threadIdx.x] : __uint_as_float(kLevelBits[threadIdx.x]);
     __syncthreads();
@@ -246,14 +248,14 @@ __global__ __launch_bounds__(kQThreads) void dq_encode_kernel(const float* __res
 
 // First level only (codes and absmax) of a range that starts on a block boundary;
 // also used by the tuned quantiser for other block sizes and for ragged ends.
-int launch_quantize_ref_range(const float* src, int64_t n, int blocksize, const float* codebook, uint8_t* packed,
-                              float* absmax, hipStream_t s) {
+int launch_quantize_ref_range(const float* src, int64_t n, int blocksize, const float* codebook, const int* skip_if,
+                              uint8_t* packed, float* absmax, hipStream_t s) {
     const int64_t nb = (n + blocksize - 1) / blocksize;
     const int64_t cap = (int64_t)compute_units() * 16;
     int64_t groups = (nb + kQWaves - 1) / kQWaves;
     groups = groups < cap ? groups : cap;
     hipLaunchKernelGGL(quantize_kernel, dim3((unsigned)groups), dim3(kQThreads), 0, s, src, n, blocksize, nb,
-                       codebook, packed, absmax);
+                       codebook, skip_if, packed, absmax);
     return record_hip(hipGetLastError());
 }
 
@@ -275,7 +277,7 @@ extern "C" int nf4_quantize_ref_codebook(const float* src, int64_t n, int blocks
 
     hipStream_t s = (hipStream_t)stream;
     const int64_t nb = (n + blocksize - 1) / blocksize;
-    int rc = launch_quantize_ref_range(src, n, blocksize, codebook, packed, absmax, s);
+    int rc = launch_quantize_ref_range(src, n, blocksize, codebook, nullptr, packed, absmax, s);
     if (rc != NF4_OK || !dq) return rc;
 
     return nf4_dq_encode(absmax, nb, dq_group, absmax_q8, scale2, offset, code2, stream);

@@ -30,7 +30,7 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(L):
     names = declared_functions()
     assert set(names) >= {"nf4_dequantize", "nf4_dequantize_dq", "nf4_dequant_gemv", "nf4_quantize_ref",
-                          "nf4_quantize", "nf4_dq_encode", "nf4_dequant_gemm", "nf4_dequant_gemm_workspace_bytes", "nf4_dequantize_batch", "nf4_dequantize_codebook",
+                          "nf4_quantize", "nf4_quantize_codebook", "nf4_dq_encode", "nf4_dequant_gemm", "nf4_dequant_gemm_workspace_bytes", "nf4_dequantize_batch", "nf4_dequantize_codebook",
                           "nf4_dequant_gemv_ws", "nf4_dequant_gemv_workspace_bytes",
                           "nf4_dequantize_dq_codebook", "nf4_quantize_ref_codebook", "nf4_last_hip_error", "nf4_status_string"}
     for name in names:
@@ -223,6 +223,24 @@ def test_quantize_argument_checks(L):
     assert f(P, 5, 64, P, None, None) == E_NULL
     assert f(P + 4, 5, 64, P, P, None) == E_ALIGN
     assert f(P, 5, 64, P + 1, P, None) == E_ALIGN
+
+
+def test_quantize_codebook_argument_checks(L):
+    f = L.nf4_quantize_codebook                  # (src, n, blocksize, codebook, packed, absmax, workspace, bytes, stream)
+    assert f(P, -1, 64, P, P, P, P, 1024, None) == E_SIZE
+    assert f(P, 5, 100, P, P, P, P, 1024, None) == E_BS
+    assert f(None, 0, 64, P, None, None, None, 0, None) == OK
+    assert f(None, 5, 64, P, P, P, P, 1024, None) == E_NULL
+    assert f(P, 5, 64, P, None, P, P, 1024, None) == E_NULL
+    assert f(P, 5, 64, P, P, None, P, 1024, None) == E_NULL
+    assert f(P, 5, 64, P, P, P, None, 1024, None) == E_NULL      # a table needs the workspace
+    assert f(P, 5, 64, P, P, P, P, 1023, None) == E_SIZE
+    assert f(P + 4, 5, 64, P, P, P, P, 1024, None) == E_ALIGN
+    assert f(P, 5, 64, P + 2, P, P, P, 1024, None) == E_ALIGN
+    assert f(P, 5, 64, P, P, P, P + 4, 1024, None) == E_ALIGN
+    # no table: nf4_quantize, whose checks answer (no workspace asked for)
+    assert f(P, 5, 100, None, P, P, None, 0, None) == E_BS
+    assert f(None, 5, 64, None, P, P, None, 0, None) == E_NULL
 
 
 def test_binding_raises_with_the_status_name():
