@@ -136,29 +136,27 @@ __global__ __launch_bounds__(128) void quant_bins_kernel(const float* __restrict
     if (tid < 17) ucode[tid] = 0;
     __syncthreads();
     if (tid < 16) {
-        const float v = level[tid];
-        if (!(__builtin_fabsf(v) < __builtin_inff())) bad = 1;     // (any writer writes the same value)
-        bool first = true;           // no lower index holds the same value
-        int rank = 0;                // distinct values below v
+        float lv[16];                // the table in registers: the loops below unroll
+#pragma unroll
+        for (int j = 0; j < 16; ++j) lv[j] = level[j];
+        uint32_t first_mask = 0;     // bit j: no lower index holds the value of level j
+#pragma unroll
         for (int j = 0; j < 16; ++j) {
             bool first_j = true;
-            for (int i = 0; i < j; ++i) first_j = first_j && !(level[i] == level[j]);
-            if (j < tid && level[j] == v) first = false;
-            if (first_j && level[j] < v) ++rank;
+#pragma unroll
+            for (int i = 0; i < j; ++i) first_j = first_j && !(lv[i] == lv[j]);
+            first_mask |= (first_j ? 1u : 0u) << j;
         }
-        if (first) {
+        const float v = level[tid];
+        if (!(__builtin_fabsf(v) < __builtin_inff())) bad = 1;     // (any writer writes the same value)
+        int rank = 0;                // distinct values below v
+#pragma unroll
+        for (int j = 0; j < 16; ++j) rank += ((first_mask >> j) & 1u) && lv[j] < v ? 1 : 0;
+        if ((first_mask >> tid) & 1u) {
             uval[rank] = v;
             ucode[rank] = tid;
         }
-        if (tid == 0) {
-            int m = 0;
-            for (int j = 0; j < 16; ++j) {
-                bool first_j = true;
-                for (int i = 0; i < j; ++i) first_j = first_j && !(level[i] == level[j]);
-                m += first_j ? 1 : 0;
-            }
-            count = m;
-        }
+        if (tid == 0) count = __builtin_popcount(first_mask);
     }
     __syncthreads();
     if (tid < 15) {
