@@ -8,20 +8,27 @@
 // row, four tokens in four registers.  So
 //   * lane (c = l / 4, i = l % 4) loads the 16 bytes of codes of row i of the group at columns 32 c .. 32 c + 31 of
 //     the wave's 512 columns: a wave-load is 4 rows x 256 contiguous bytes, and the waves of a workgroup that share
-//     the rows read them side by side (the 16-row tiles of the big MFMA shapes would be 64 bytes per row);
-//   * the lane's 32 activations per token (token i, its own columns) stay in 16 registers for the whole pass over
+//     the rows read them side by side (the 16-row tiles of the big MFMA shapes would be 64 bytes per row, and at
+//     block size 64 could not keep the 32 k of a step in one quantisation block without moving codes between lanes);
+//   * the lane's 32 activations (token i, its own columns) stay in 32 registers, each pair twice, for the whole pass over
 //     the rows: no activation traffic in the loop, nothing goes through LDS except the lookups;
 //   * a lane's 32 columns lie in one quantisation block and its results are those of its own row, so the block scale
 //     is applied by the lane that owns it, in FP32, to the four sums of eight 4-wide steps;
 //   * every level enters as two FP16 terms (the split table of nf4_device.hpp: hi + lo = the level to about 2^-22),
 //     two MFMAs per step, as on the other matrix-core paths of the GEMV; accumulation in FP32;
-//   * the cost does not depend on the number of tokens (1 to 4): 16 lookups, 16 permutes, 16 small MFMAs and about
-//     a dozen other vector instructions per 2048 weights, against 32 B multiply-adds on the vector ALU.
+//   * the cost does not depend on the number of tokens (1 to 4): 16 lookups, 16 permutes, 16 small MFMAs (8 cycles
+//     each) and about 33 other vector instructions per 2048 weights and wave, against 32 B multiply-adds, 16 permutes
+//     and about 11 others on the vector ALU: slower than the one-token kernel, level with two tokens, ahead from three.
 // A workgroup is KSW column waves x RS row streams (at most 16 waves) and owns a contiguous range of rows; when K is
-// wider than its waves (more than 8192 columns) it passes over the rows once per group of columns, reloading the 16
-// activation registers, and adds into the same LDS slots.  Per (row, token) the sums of the sixteen 32-column pieces
-// of a wave meet by two DPP adds down to one per 16 lanes; those go to LDS and are added in a fixed order at the end
-// (deterministic).  Block scales are decoded once per workgroup into LDS as in the one-token kernel.
+// wider than its waves it passes over the rows once per group of columns, reloading the 32 activation registers, and
+// adds into the same LDS slots; the ring of four loads per wave keeps running from one pass into the next.  Per
+// (row, token) the sums of the sixteen 32-column pieces of a wave meet by two DPP adds down to one per 16 lanes;
+// those go to LDS and are added in a fixed order at the end (deterministic).  Block scales are decoded once per
+// workgroup into LDS as in the one-token kernel.
+// Measured on the 70B MLP shapes (8192 x 28672 / 28672 x 8192, eight weight copies cycled): 32-34 / 34-36 us at three
+// tokens, 33.5-36.5 / 36-37.4 us at four; with the code loads alone 25.5-28.6 us, with everything but them 27-28 us:
+// the kernel is bound by instruction issue (a SIMD's vector pipe is taken for 11-12 k of the 14-18 k issue slots a
+// wave lives, a fifth of the instructions being MFMAs that hold it for two).
 #include "nf4_device.hpp"
 #include "nf4_host.hpp"
 
