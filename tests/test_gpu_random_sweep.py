@@ -61,8 +61,10 @@ def test_random_quantize_cases():
 
 def test_random_codebook_cases():
     """Random codebooks (any order, any magnitude, repeated and zero levels), block sizes and second-level
-    group sizes: quantise with the reference quantiser and dequantise, both against the oracle."""
+    group sizes: quantise with the reference quantiser and with the tuned one, and dequantise, all against the
+    oracle."""
     rng = np.random.Generator(np.random.PCG64(2026))
+    tuned_path_taken = 0
     for case in range(60):
         bs = int(rng.choice([64, 128, 256, 1024, 4096]))
         group = int(rng.choice([1, 2, 32, 256, 2048]))
@@ -83,6 +85,15 @@ def test_random_codebook_cases():
         tag = f"case {case}: n={n} bs={bs} group={group}"
         assert np.array_equal(bufs["packed"].cpu().numpy()[:p.size], p), tag
         assert np.array_equal(bufs["absmax"].cpu().numpy()[:a.size], a), tag
+        # the tuned quantiser with the same table: thresholds found on the device, or the reference kernel inside the call
+        tuned = nf4.alloc_quantized(n, bs)
+        tuned["packed"].fill_(0xCD)
+        wsq = torch.full((nf4.QUANTIZE_CODEBOOK_WORKSPACE_BYTES,), 0xFF, dtype=torch.uint8, device="cuda")
+        nf4.nf4_quantize_codebook(dev(w), n, bs, dcb, tuned["packed"], tuned["absmax"], wsq)
+        torch.cuda.synchronize()
+        assert np.array_equal(tuned["packed"].cpu().numpy()[:p.size], p), tag + " (tuned)"
+        assert np.array_equal(tuned["absmax"].cpu().numpy()[:a.size], a), tag + " (tuned)"
+        tuned_path_taken += int(wsq[520:524].cpu().numpy().view(np.int32)[0])
         assert np.array_equal(bufs["absmax_q8"].cpu().numpy()[:q8.size], q8), tag
         assert np.array_equal(bufs["scale2"].cpu().numpy()[:s2.size], s2), tag
         assert np.array_equal(bufs["offset"].cpu().numpy(), off), tag
@@ -95,6 +106,8 @@ def test_random_codebook_cases():
         want = oracle.dequantize_dq_codebook(p, q8, s2, off, c2, group, cb, n, blocksize=bs, out_dtype=odt)
         assert mismatches(bits(out), want, bf16) == 0, tag
         assert guard_intact(whole, n), tag
+    print(f"tuned quantiser: {tuned_path_taken} of 60 random tables carried by thresholds, the rest by the reference kernel")
+    assert 5 <= tuned_path_taken <= 55                             # both ways are exercised
 
 
 def test_random_gemv_and_gemm_cases():
