@@ -23,6 +23,7 @@ the 70B MLP shapes, the tuned quantiser, other formats, a Qwen3-32B layer replay
 are reported under `extra`.
 """
 import argparse
+import glob
 import json
 import os
 import sys
@@ -123,6 +124,7 @@ def main():
     for _ in range(args.steps):
         one_step()
     ev1.record(stream)
+    clocks = read_gpu_clocks()                           # the last launches are still queued: clocks under load
     stream.synchronize()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
@@ -142,6 +144,7 @@ def main():
         "avg_launch_us": round(avg_launch_us, 3),
         "algorithmic_bytes_per_launch": round(bytes_per_launch, 1),
         "launches": launches,
+        "clocks_under_load": clocks,
     }
     # HBM bytes per launch from the rocprofv3 counter runs recorded in profiles/ (counters cannot be read inside
     # this run).  The record names the kernel source it was measured on; if the source has changed since, the
@@ -208,7 +211,27 @@ def kernel_source_hash():
     return h.hexdigest()
 
 
-def time_on_stream(torch, stream, fn, iters, warmup=2):
+def read_gpu_clocks():
+    """Shader and memory clock in MHz as the driver reports them at this moment (the starred line of
+    pp_dpm_sclk / pp_dpm_mclk in sysfs), or None where the files cannot be read.  Clocks are not locked on these
+    boxes; called while timed work is still in flight, it shows the clocks that work ran at."""
+    out = {}
+    for key, name in (("sclk_mhz", "pp_dpm_sclk"), ("mclk_mhz", "pp_dpm_mclk")):
+        out[key] = None
+        for path in sorted(glob.glob(f"/sys/class/drm/card*/device/{name}")):
+            try:
+                with open(path) as f:
+                    for line in f:
+                        if line.rstrip().endswith("*"):
+                            out[key] = int(line.split(":")[1].strip().split("M")[0])
+            except (OSError, ValueError, IndexError):
+                pass
+            if out[key] is not None:
+                break
+    return out
+
+
+def time_on_stream(torch, stream, fn, iters, warmup=2, clocks=None):
     for _ in range(warmup):
         fn()
     stream.synchronize()
@@ -217,6 +240,8 @@ def time_on_stream(torch, stream, fn, iters, warmup=2):
     for _ in range(iters):
         fn()
     e1.record(stream)
+    if clocks is not None:                               # the queue is still draining: the clocks under this load
+        clocks.update(read_gpu_clocks())
     stream.synchronize()
     return e0.elapsed_time(e1) * 1e3 / iters           # microseconds per call
 
@@ -397,8 +422,9 @@ def leg_gemv(torch, nf4, synth, stream, gen, src):
                 for b in copies:
                     nf4.nf4_dequant_gemv(b["packed"], b["absmax_q8"], b["scale2"], b["offset"], b["code2"], 64,
                                          N, K, x, B, y, stream=stream)
-            us = time_on_stream(torch, stream, run, 5) / len(copies)
-            res[f"N{N}_K{K}_B{B}"] = gemv_entry(n, B, us, gemv_kernel_name(N, K, B, False))
+            clk = {}
+            us = time_on_stream(torch, stream, run, 5, clocks=clk) / len(copies)
+            res[f"N{N}_K{K}_B{B}"] = dict(gemv_entry(n, B, us, gemv_kernel_name(N, K, B, False)), sclk_mhz=clk.get("sclk_mhz"))
             if B >= 3:      # with a caller workspace K is split across workgroups (nf4_dequant_gemv_ws)
                 ws = torch.empty(nf4.nf4_dequant_gemv_workspace_bytes(N, K, B), dtype=torch.uint8, device=dev)
 
@@ -406,9 +432,10 @@ def leg_gemv(torch, nf4, synth, stream, gen, src):
                     for b in copies:
                         nf4.nf4_dequant_gemv_ws(b["packed"], b["absmax_q8"], b["scale2"], b["offset"], b["code2"], 64,
                                                 N, K, x, B, y, ws, stream=stream)
-                us = time_on_stream(torch, stream, run_ws, 5) / len(copies)
+                clk = {}
+                us = time_on_stream(torch, stream, run_ws, 5, clocks=clk) / len(copies)
                 res[f"ws_N{N}_K{K}_B{B}"] = dict(gemv_entry(n, B, us, gemv_kernel_name(N, K, B, True)),
-                                                 workspace_bytes=int(ws.numel()))
+                                                 workspace_bytes=int(ws.numel()), sclk_mhz=clk.get("sclk_mhz"))
         # the matrix-core variant (weights rounded to FP16 in registers), the paper's batch range
         for B in GEMM_BATCHES:
             gen.manual_seed(6100 + B)
