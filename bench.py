@@ -315,8 +315,29 @@ def leg_dq(torch, nf4, synth, stream, gen, src):
                                   stream=stream)
     us = time_on_stream(torch, stream, run, 10) / layers
     gbps = elems / layers * BYTES_PER_ELEM_DQ / (us * 1e-6) / 1e9
-    return {"elements_per_layer": elems // layers, "layers": layers, "us_per_layer": round(us, 2), "GB/s": round(gbps, 1),
-            "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4)}
+    res = {"elements_per_layer": elems // layers, "layers": layers, "us_per_layer": round(us, 2), "GB/s": round(gbps, 1),
+           "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4)}
+    # the same layers with one launch each (nf4_dequantize_batch into a layer-sized buffer that the layers reuse):
+    # what the fill and drain of six launches per layer cost, four of them on tensors of 22 and 44 MB of output
+    per_layer = len(synth.GEMMA_27B)
+    offs, total = [], 0
+    for n, _ in tensors[:per_layer]:
+        offs.append(total)
+        total += (n + 127) // 128 * 128
+    arena = torch.empty(total, dtype=torch.bfloat16, device=dev)
+    batches = [[dict(packed=b["packed"], absmax_q8=b["absmax_q8"], scale2=b["scale2"], offset=b["offset"],
+                     code2=b["code2"], out=arena[offs[i]:offs[i] + n], n=n)
+                for i, (n, b) in enumerate(tensors[layer * per_layer:(layer + 1) * per_layer])]
+               for layer in range(layers)]
+
+    def run_batched():
+        for items in batches:
+            nf4.nf4_dequantize_batch(items, 64, stream=stream)
+    us_b = time_on_stream(torch, stream, run_batched, 10) / layers
+    gbps_b = elems / layers * BYTES_PER_ELEM_DQ / (us_b * 1e-6) / 1e9
+    res["one_launch_per_layer"] = {"us_per_layer": round(us_b, 2), "GB/s": round(gbps_b, 1),
+                                   "frac_of_hbm_peak": round(gbps_b / HBM_PEAK_GBPS, 4)}
+    return res
 
 
 def leg_formats(torch, nf4, synth, stream, gen, src):
