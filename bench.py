@@ -231,19 +231,25 @@ def read_gpu_clocks():
     return out
 
 
-def time_on_stream(torch, stream, fn, iters, warmup=2, clocks=None):
+def time_on_stream(torch, stream, fn, iters, warmup=2, clocks=None, batches=1):
+    """Microseconds per call of fn: HIP events on the stream around `iters` calls; with batches > 1 the median of
+    that many such measurements (the short GEMV legs vary by 10 % from one batch of 40 launches to the next)."""
     for _ in range(warmup):
         fn()
     stream.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record(stream)
-    for _ in range(iters):
-        fn()
-    e1.record(stream)
-    if clocks is not None:                               # the queue is still draining: the clocks under this load
-        clocks.update(read_gpu_clocks())
-    stream.synchronize()
-    return e0.elapsed_time(e1) * 1e3 / iters           # microseconds per call
+    times = []
+    for _ in range(batches):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(iters):
+            fn()
+        e1.record(stream)
+        if clocks is not None:                           # the queue is still draining: the clocks under this load
+            clocks.update(read_gpu_clocks())
+        stream.synchronize()
+        times.append(e0.elapsed_time(e1) * 1e3 / iters)
+    times.sort()
+    return times[len(times) // 2]
 
 
 def batched_stream(torch, nf4, stream, tensors, names, layers, bytes_per_step):
@@ -444,7 +450,7 @@ def leg_gemv(torch, nf4, synth, stream, gen, src):
                     nf4.nf4_dequant_gemv(b["packed"], b["absmax_q8"], b["scale2"], b["offset"], b["code2"], 64,
                                          N, K, x, B, y, stream=stream)
             clk = {}
-            us = time_on_stream(torch, stream, run, 5, clocks=clk) / len(copies)
+            us = time_on_stream(torch, stream, run, 5, clocks=clk, batches=5) / len(copies)
             res[f"N{N}_K{K}_B{B}"] = dict(gemv_entry(n, B, us, gemv_kernel_name(N, K, B, False)), sclk_mhz=clk.get("sclk_mhz"))
             if B >= 3:      # with a caller workspace K is split across workgroups (nf4_dequant_gemv_ws)
                 ws = torch.empty(nf4.nf4_dequant_gemv_workspace_bytes(N, K, B), dtype=torch.uint8, device=dev)
@@ -454,7 +460,7 @@ def leg_gemv(torch, nf4, synth, stream, gen, src):
                         nf4.nf4_dequant_gemv_ws(b["packed"], b["absmax_q8"], b["scale2"], b["offset"], b["code2"], 64,
                                                 N, K, x, B, y, ws, stream=stream)
                 clk = {}
-                us = time_on_stream(torch, stream, run_ws, 5, clocks=clk) / len(copies)
+                us = time_on_stream(torch, stream, run_ws, 5, clocks=clk, batches=5) / len(copies)
                 res[f"ws_N{N}_K{K}_B{B}"] = dict(gemv_entry(n, B, us, gemv_kernel_name(N, K, B, True)),
                                                  workspace_bytes=int(ws.numel()), sclk_mhz=clk.get("sclk_mhz"))
         # the matrix-core variant (weights rounded to FP16 in registers), the paper's batch range
@@ -467,7 +473,7 @@ def leg_gemv(torch, nf4, synth, stream, gen, src):
                 for b in copies:
                     nf4.nf4_dequant_gemm(b["packed"], b["absmax_q8"], b["scale2"], b["offset"], b["code2"], 64,
                                          N, K, x, B, y, stream=stream)
-            us = time_on_stream(torch, stream, run_mm, 5) / len(copies)
+            us = time_on_stream(torch, stream, run_mm, 5, batches=3) / len(copies)
             gbps = n * GEMV_BYTES_PER_ELEM / (us * 1e-6) / 1e9
             res[f"mfma_N{N}_K{K}_B{B}"] = {"us": round(us, 2), "GB/s": round(gbps, 1),
                                            "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
@@ -479,7 +485,7 @@ def leg_gemv(torch, nf4, synth, stream, gen, src):
                 for b in copies:
                     nf4.nf4_dequant_gemm(b["packed"], b["absmax_q8"], b["scale2"], b["offset"], b["code2"], 64,
                                          N, K, x, B, y, workspace=ws, stream=stream)
-            us = time_on_stream(torch, stream, run_sk, 5) / len(copies)
+            us = time_on_stream(torch, stream, run_sk, 5, batches=3) / len(copies)
             gbps = n * GEMV_BYTES_PER_ELEM / (us * 1e-6) / 1e9
             res[f"mfma_splitk_N{N}_K{K}_B{B}"] = {"us": round(us, 2), "GB/s": round(gbps, 1),
                                                   "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4),
